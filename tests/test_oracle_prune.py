@@ -1,0 +1,155 @@
+"""Pins of the prune/free oracle: Algorithm 1's argmin / ReleaseKVCache / set removal, k times."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2601_09093_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+P = 16
+
+
+def _layout(seed, N=8, prompt=32, lo=33, hi=200, slack=1.3):
+    r = wl.rng_for(seed, 0)
+    lens = r.integers(lo, hi + 1, N)
+    return wl.build_layout(lens, prompt, P, wl.rng_for(seed, 1), slack=slack)
+
+
+def _scores(seed, N):
+    return wl.rng_for(seed, 2).uniform(0, 1, N).astype(np.float32)
+
+
+def _run(lay, scores, k):
+    rc = lay.refcounts.copy(); bt = lay.block_tables.copy(); sl = lay.seq_lens.copy()
+    pruned, freed = oracle.prune_free(scores, k, rc, bt, sl, P)
+    return pruned, freed, rc, bt, sl
+
+
+def test_hand_computed_bottom_k():
+    g = json.load(open(os.path.join(GOLD, "bottomk_hand.json")))
+    for c in g["cases"]:
+        scores = np.array([float(x) for x in c["scores"]], np.float32)
+        N = scores.size
+        live = np.array(c["live"])
+        lens = np.where(live == 1, 20 + np.arange(N), 0)
+        lay = wl.build_layout(lens, 0, P, wl.rng_for(1, 1))
+        pruned, *_ = _run(lay, scores, c["k"])
+        assert pruned.tolist() == c["pruned"], c
+
+
+@pytest.mark.parametrize("seed,k", [(31, 1), (32, 3), (33, 8), (34, 0)])
+def test_brute_force_sorted_selection(seed, k):
+    lay = _layout(seed)
+    scores = _scores(seed, 8)
+    scores[3] = scores[5]                                   # a tie
+    lay.seq_lens[6] = 0; lay.refcounts[lay.block_tables[6][lay.block_tables[6] >= 0]] -= 1
+    lay.block_tables[6] = -1                                # a dead trace
+    k = min(k, 7)
+    pruned, *_ = _run(lay, scores, k)
+    live = [i for i in range(8) if lay.seq_lens[i] > 0]
+    assert pruned.tolist() == sorted(live, key=lambda i: (scores[i], i))[:k]
+
+
+def test_k1_is_algorithm_1_argmin():
+    lay = _layout(35)
+    scores = _scores(35, 8)
+    pruned, freed, rc, bt, sl = _run(lay, scores, 1)
+    t = int(np.argmin(scores))
+    assert pruned.tolist() == [t]
+    nb = (lay.seq_lens[t] + P - 1) // P
+    own = lay.block_tables[t, :nb]
+    assert sorted(freed.tolist()) == sorted(own[2:].tolist())   # tail pages freed, 2 prompt pages kept
+    assert np.all(rc[own[:2]] == 7) and np.all(rc[own[2:]] == 0)
+    assert np.all(bt[t] == -1) and sl[t] == 0
+    keep = np.arange(8) != t
+    assert np.array_equal(bt[keep], lay.block_tables[keep]) and np.array_equal(sl[keep], lay.seq_lens[keep])
+
+
+@pytest.mark.parametrize("k", [1, 4, 7, 8])
+def test_conservation_and_freed_set_invariants(k):
+    lay = _layout(36)
+    scores = _scores(36, 8)
+    pruned, freed, rc, bt, sl = _run(lay, scores, k)
+    nb = (lay.seq_lens.astype(np.int64) + P - 1) // P
+    assert lay.refcounts.sum() - rc.sum() == nb[pruned].sum()
+    assert np.all(np.diff(freed) > 0)                       # ascending, no duplicates
+    assert np.all(rc[freed] == 0) and np.all(lay.refcounts[freed] > 0)
+    surviving = bt[bt >= 0]
+    assert not np.intersect1d(surviving, freed).size
+    assert np.all(rc[surviving] > 0)
+    # refcount of every page == number of surviving rows that reference it
+    want = np.zeros_like(rc); np.add.at(want, surviving, 1)
+    assert np.array_equal(rc, want)
+    prompt_pages = lay.block_tables[0, :2]
+    assert np.all(rc[prompt_pages] == 8 - k)
+    assert np.isin(prompt_pages, freed).all() == (k == 8)
+    if k == 8:
+        assert sorted(freed.tolist()) == np.nonzero(lay.refcounts)[0].tolist()
+
+
+def test_two_rounds_equal_one_round():
+    lay = _layout(37)
+    scores = _scores(37, 8)
+    p_all, f_all, rc_all, bt_all, sl_all = _run(lay, scores, 5)
+    rc = lay.refcounts.copy(); bt = lay.block_tables.copy(); sl = lay.seq_lens.copy()
+    p1, f1 = oracle.prune_free(scores, 2, rc, bt, sl, P)
+    p2, f2 = oracle.prune_free(scores, 3, rc, bt, sl, P)
+    assert np.concatenate([p1, p2]).tolist() == p_all.tolist()
+    assert sorted(np.concatenate([f1, f2]).tolist()) == f_all.tolist()
+    assert np.array_equal(rc, rc_all) and np.array_equal(bt, bt_all) and np.array_equal(sl, sl_all)
+
+
+def test_freed_list_is_sorted_by_page_id_not_by_trace():
+    lay = _layout(38, N=4, prompt=0, lo=40, hi=90)
+    scores = np.array([0.4, 0.1, 0.3, 0.2], np.float32)
+    pruned, freed, *_ = _run(lay, scores, 3)
+    assert pruned.tolist() == [1, 3, 2]
+    pages = np.concatenate([lay.block_tables[t][lay.block_tables[t] >= 0] for t in (1, 3, 2)])
+    assert freed.tolist() == sorted(pages.tolist())
+
+
+def test_config1_prune_bottom_one_of_four():
+    w = wl.make_workload(1, kv=False)
+    scores = np.array([0.6, 0.2, 0.9, 0.4], np.float32)
+    rc = w.layout.refcounts.copy(); bt = w.layout.block_tables.copy(); sl = w.layout.seq_lens.copy()
+    pruned, freed = oracle.prune_free(scores, 1, rc, bt, sl, P)
+    assert pruned.tolist() == [1]
+    assert np.all(rc[w.layout.block_tables[0, :4]] == 3)    # prompt's 4 pages: 4 -> 3
+    assert freed.size == (w.layout.seq_lens[1] + 15) // 16 - 4
+
+
+def test_errors_leave_state_untouched():
+    lay = _layout(39)
+    scores = _scores(39, 8)
+    for mutate, name in [
+        (lambda rc, bt, sl, sc: sc.__setitem__(2, np.nan), "ENAN"),
+        (lambda rc, bt, sl, sc: bt.__setitem__((int(np.argmin(sc)), 1), lay.NP), "EPAGE"),
+        (lambda rc, bt, sl, sc: rc.__setitem__(bt[int(np.argmin(sc)), 3], 0), "EREFCOUNT"),
+        (lambda rc, bt, sl, sc: sl.__setitem__(0, lay.MAXB * P + 1), "ELEN"),
+    ]:
+        rc = lay.refcounts.copy(); bt = lay.block_tables.copy(); sl = lay.seq_lens.copy(); sc = scores.copy()
+        mutate(rc, bt, sl, sc)
+        rc0, bt0, sl0 = rc.copy(), bt.copy(), sl.copy()
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.prune_free(sc, 1, rc, bt, sl, P)
+        assert e.value.name == name
+        assert np.array_equal(rc, rc0) and np.array_equal(bt, bt0) and np.array_equal(sl, sl0)
+    with pytest.raises(oracle.OracleError) as e:           # k larger than the live set
+        _run(lay, scores, 9)
+    assert e.value.name == "EINVAL"
+    # a NaN on a dead trace is ignored
+    sc = scores.copy(); sc[4] = np.nan
+    sl = lay.seq_lens.copy(); sl[4] = 0
+    rc = lay.refcounts.copy(); bt = lay.block_tables.copy()
+    p, _ = oracle.prune_free(sc, 7, rc, bt, sl, P)
+    assert 4 not in p.tolist()
+
+
+def test_duplicate_page_in_one_row_is_released_once_per_reference():
+    bt = np.array([[0, 0, 1]], np.int32); sl = np.array([48], np.int32)
+    rc = np.array([2, 1, 5], np.int32)
+    pruned, freed = oracle.prune_free(np.array([0.5], np.float32), 1, rc, bt, sl, P)
+    assert pruned.tolist() == [0] and freed.tolist() == [0, 1] and rc.tolist() == [0, 0, 5]
