@@ -1,0 +1,164 @@
+/*
+ * libstep -- C ABI of the decode-step hot path of STEP (arxiv 2601.09093) on one MI355X (gfx950).
+ *
+ * One decode step over N parallel reasoning traces of one prompt is three calls, in this order:
+ *   paged_decode_attn   the attention inside NextToken(t) of Algorithm 1, for all live traces,
+ *   step_score          y = f(h) for the traces at a step boundary, then "Update score_t"
+ *                       (Section 4.1 equation; Section 4.3 running average),
+ *   prune_free          argmin score_t / ReleaseKVCache / T <- T \ {t*} of Algorithm 1, k times.
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer owned by the caller unless it says "host".  The library
+ *     allocates nothing; scratch memory comes in through `workspace` (256-byte aligned).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on it and never synchronise; arrays may be reused once the stream reaches that point.
+ *   - Return value: STEP_OK, or an error found on the host before anything was enqueued.
+ *   - Errors only the device can see (a page id outside the pool, a length past the block-table
+ *     row, a boundary row outside `hidden`, a NaN score, a refcount that would go negative) are
+ *     reported in `*status` (device int32, caller-zeroed): the first non-zero code wins and stays.
+ *     A call that reports such an error produces unspecified outputs but never reads or writes
+ *     outside the arrays described here.  status may be NULL (errors are then dropped).
+ *   - bf16 arrays are passed as uint16_t bit patterns.
+ */
+#ifndef STEP_H
+#define STEP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum step_error {
+    STEP_OK = 0,
+    STEP_EINVAL = 1,     /* host: bad dimension, null or misaligned pointer, k > N              */
+    STEP_EWORKSPACE = 2, /* host: workspace smaller than the matching *_workspace_bytes()       */
+    STEP_ELAUNCH = 3,    /* host: the HIP runtime refused a launch (hipGetLastError was non-zero)*/
+    STEP_EPAGE = 16,     /* device: block-table entry outside [0, NP) among a trace's used pages */
+    STEP_ELEN = 17,      /* device: seq_lens[i] < 0 or > MAXB * P                                */
+    STEP_EINDEX = 18,    /* device: boundary_idx outside [0, R) or trace_of outside [0, N)       */
+    STEP_ENAN = 19,      /* device: NaN score on a live trace                                    */
+    STEP_EREFCOUNT = 20, /* device: a released page had refcount <= 0                            */
+    STEP_EKLIVE = 21     /* device: k larger than the number of live traces                      */
+};
+
+/* Human-readable name of an error code (host pointer to a static string). */
+const char *step_strerror(int code);
+/* Library version, "major.minor". */
+const char *step_version(void);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Paged grouped-query decode attention (the attention of NextToken in Algorithm 1).           */
+/* ------------------------------------------------------------------------------------------ */
+
+typedef struct {
+    int32_t N;    /* traces                                                                     */
+    int32_t Hq;   /* query heads                                                                */
+    int32_t Hkv;  /* KV heads; Hq % Hkv == 0, group size G = Hq / Hkv in {1, 2, 4, 8}           */
+    int32_t D;    /* head dimension, 64 or 128                                                  */
+    int32_t P;    /* tokens per page, must be 16                                                */
+    int32_t MAXB; /* row width of block_tables                                                  */
+    int32_t NP;   /* pages in the pool                                                          */
+    float scale;  /* logit scale, normally 1/sqrt(D)                                            */
+} step_attn_dims;
+
+/* Bytes of workspace paged_decode_attn needs for these dims (host function, no device work). */
+size_t step_attn_workspace_bytes(const step_attn_dims *dims);
+
+/*
+ * For every trace i with L = seq_lens[i] > 0 and every query head h (KV head g = h / G):
+ *   x_t = scale * <q[i][h], K[page(t)][g][t % P]>,  t in [0, L),  page(t) = block_tables[i][t / P]
+ *   out[i][h] = sum_t softmax(x)_t * V[page(t)][g][t % P]          rounded to bf16 (nearest even).
+ * The query is the newest token, whose K/V row is already in the cache: L includes it, no mask.
+ * A trace with L == 0 (pruned) gets a zero output row.  Pages may be shared between traces (the
+ * prompt's); slots past a trace's last token and unreferenced pages are never read into a result.
+ *
+ *   q            [N][Hq][D]        bf16, 16-byte aligned
+ *   k_pages      [NP][Hkv][P][D]   bf16, 16-byte aligned (one (page, head) tile is contiguous)
+ *   v_pages      [NP][Hkv][P][D]   bf16, same layout, separate array
+ *   block_tables [N][MAXB]         int32, -1 in unused entries
+ *   seq_lens     [N]               int32
+ *   out          [N][Hq][D]        bf16, written for every trace
+ *   workspace    >= step_attn_workspace_bytes(dims), 256-byte aligned; holds split-K partials
+ * Arithmetic: exact bf16 products, fp32 accumulation, fp32 softmax; the softmax weights are kept
+ * in fp32.  Result within 2e-2 max-abs of the float64 definition for N(0,1) inputs.
+ */
+int paged_decode_attn(const step_attn_dims *dims, const uint16_t *q, const uint16_t *k_pages,
+                      const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
+                      uint16_t *out, void *workspace, size_t workspace_bytes, int32_t *status, void *stream);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Step scorer + running-mean trace score (Section 4.1 equation, Section 4.3 equation).        */
+/* ------------------------------------------------------------------------------------------ */
+
+enum step_activation { STEP_ACT_RELU = 0 /* the paper's (Table 5) */, STEP_ACT_GELU = 1 /* exact erf form */ };
+
+typedef struct {
+    int32_t R;   /* rows of hidden                                                              */
+    int32_t d;   /* hidden size of the LLM, multiple of 128                                     */
+    int32_t m;   /* width of the scorer's hidden layer, multiple of 16                          */
+    int32_t B;   /* step boundaries in this call (may be 0)                                     */
+    int32_t N;   /* traces (length of score_sum / score_cnt / scores); 0 if those are NULL      */
+    int32_t act; /* enum step_activation                                                        */
+} step_score_dims;
+
+size_t step_score_workspace_bytes(const step_score_dims *dims);
+
+/*
+ * For b in [0, B): x = hidden[boundary_idx[b]];  z = W1 x + b1;  logits[b] = <W2, act(z)> + b2;
+ * probs[b] = 1 / (1 + exp(-logits[b])).
+ * Then, if the running-mean state is passed (score_sum and score_cnt not NULL; trace_of is then
+ * required when B > 0), for b = 0 .. B-1 in this order: t = trace_of[b];
+ * score_sum[t] += probs[b] (fp32); score_cnt[t] += 1; and finally, if scores is not NULL, for every
+ * t in [0, N): scores[t] = score_cnt[t] > 0 ? score_sum[t] / score_cnt[t] (IEEE fp32 divide) : +inf
+ * (a trace with no finished step yet is pruned after every scored one).
+ *
+ *   hidden [R][d] bf16 (16-byte aligned rows) | boundary_idx [B] int32 | W1 [m][d] bf16 row-major
+ *   b1 [m] fp32 | W2 [m] bf16 | b2 [1] fp32 (device) | logits, probs [B] fp32
+ *   trace_of [B] int32 | score_sum [N] fp32, score_cnt [N] int32 (in/out, or both NULL) | scores [N] fp32 or NULL
+ * Arithmetic: bf16 products on the matrix cores with fp32 accumulation; the hidden activations
+ * stay fp32.  logits within 1e-3 max-abs of the float64 definition.
+ */
+int step_score(const step_score_dims *dims, const uint16_t *hidden, const int32_t *boundary_idx,
+               const uint16_t *W1, const float *b1, const uint16_t *W2, const float *b2,
+               float *logits, float *probs, const int32_t *trace_of, float *score_sum,
+               int32_t *score_cnt, float *scores, void *workspace, size_t workspace_bytes,
+               int32_t *status, void *stream);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Prune the k lowest-scoring live traces and release their pages (Algorithm 1, k times).      */
+/* ------------------------------------------------------------------------------------------ */
+
+size_t step_prune_workspace_bytes(int32_t N, int32_t MAXB, int32_t NP);
+
+/*
+ * Live traces are those with seq_lens[i] > 0.  The k live traces with the smallest
+ * (scores[i], i) are pruned (ties go to the lower index; -0 == +0), reported in that order.
+ * For each pruned t and each j < ceil(seq_lens[t] / P): p = block_tables[t][j], refcounts[p] -= 1;
+ * a page whose count reaches 0 is freed.  freed_pages receives the freed ids in ascending order,
+ * *n_freed their number.  Then block_tables[t][*] = -1 and seq_lens[t] = 0.
+ * k == 0 is a no-op (*n_freed = 0).  On a device-reported error the selection is abandoned
+ * before any array is modified when the error is in the selection (STEP_ENAN, STEP_EKLIVE,
+ * STEP_ELEN); a bad page id or refcount met during release is reported and that page skipped.
+ *
+ *   scores [N] fp32 | refcounts [NP] int32 in/out | block_tables [N][MAXB] int32 in/out
+ *   seq_lens [N] int32 in/out | pruned [k] int32 out | freed_pages [min(NP, k*MAXB)] int32 out
+ *   n_freed [1] int32 out | workspace >= step_prune_workspace_bytes(N, MAXB, NP)
+ * Integer work only: every output is bit-exact with the definition.  N <= 4096.
+ */
+int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k,
+               int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
+               int32_t *freed_pages, int32_t *n_freed, void *workspace, size_t workspace_bytes,
+               int32_t *status, void *stream);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Measurement aid: a plain copy kernel of known size (dst[i] = src[i], 16-byte units), used   */
+/* to calibrate profiler byte counters against known traffic.  bytes % 16 == 0.               */
+/* ------------------------------------------------------------------------------------------ */
+int step_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STEP_H */

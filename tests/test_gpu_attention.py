@@ -1,0 +1,195 @@
+"""GPU parity of paged_decode_attn (through the C ABI) against the float64 oracle, element by element
+on the same seeded bytes.  Bar: max-abs 2e-2 on bf16 outputs (fp32 accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_09093_amd import binding, workloads as wl
+from tests.gpu_util import DEV, dev, dev_bits, host_f32_of_bf16, host_bits, new_status
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+P = 16
+
+
+def run_gpu(q, k, v, bt, sl, scale=None, expect_status=0):
+    st = new_status()
+    out = binding.paged_decode_attn(dev_bits(q), dev_bits(k), dev_bits(v), dev(bt), dev(sl), scale=scale, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == expect_status, binding.ERROR_NAMES.get(int(st.item()))
+    return host_f32_of_bf16(out)
+
+
+def check(q, k, v, bt, sl, scale=None, tol=TOL):
+    got = run_gpu(q, k, v, bt, sl, scale)
+    want = oracle.paged_decode_attn(q, k, v, bt, sl, scale)
+    assert np.all(np.isfinite(got))
+    err = np.abs(got - want)
+    # bf16 rounding of the output (2^-9 relative) plus fp32 accumulation noise
+    assert np.all(err <= 2.0 ** -8 * np.abs(want) + 2e-3), float(err.max())
+    assert err.max() <= tol
+    return got, want
+
+
+def build(seed, lens, Hq, Hkv, D, prompt=0, slack=1.3, poison=True, qstd=1.0):
+    lay = wl.build_layout(np.asarray(lens), prompt, P, wl.rng_for(seed, 0), slack=slack)
+    N = len(lens)
+    q = wl.normal_bf16(wl.rng_for(seed, 1), (N, Hq, D), qstd)
+    k = wl.normal_bf16(wl.rng_for(seed, 2), (lay.NP, Hkv, P, D))
+    v = wl.normal_bf16(wl.rng_for(seed, 3), (lay.NP, Hkv, P, D))
+    if poison:
+        wl.poison_unused(k, v, lay, P)
+    return lay, q, k, v
+
+
+def test_config1_tiny_decode_step():
+    w = wl.make_workload(1, poison=True)
+    check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
+    w2 = wl.make_workload(1, poison=True, permute=False)
+    check(w2.q, w2.k_pages, w2.v_pages, w2.layout.block_tables, w2.layout.seq_lens)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_all_head_shapes(D, G):
+    Hkv = 2
+    lens = [1, 15, 16, 17, 100, 333, 512, 513, 1100]
+    lay, q, k, v = build(100 + D + G, lens, G * Hkv, Hkv, D)
+    check(q, k, v, lay.block_tables, lay.seq_lens)
+
+
+def test_ragged_edges_around_page_and_chunk_boundaries():
+    lens = [0, 1, 2, 15, 16, 17, 31, 32, 33, 511, 512, 513, 527, 528, 529, 1023, 1024, 1025, 1537, 0, 2049]
+    lay, q, k, v = build(7, lens, 8, 2, 128)
+    got, _ = check(q, k, v, lay.block_tables, lay.seq_lens)
+    assert np.all(got[0] == 0) and np.all(got[19] == 0)          # dead traces give zero rows
+    vf = wl.bf16_bits_to_f32(v)
+    assert np.array_equal(got[1, 5], vf[lay.block_tables[1, 0], 1, 0])   # L = 1: exactly v_0
+
+
+def test_scaled_down_config2_shared_prompt():
+    w = wl.make_workload(2, N=6, tail=(100, 2500), poison=True)
+    assert w.shape.Hq == 32 and w.shape.Hkv == 8 and w.shape.D == 128
+    check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
+
+
+def test_scaled_down_config3_fragmented_pool():
+    w = wl.make_workload(3, N=8, tail=(700, 3000), poison=True)
+    assert w.layout.NP > w.layout.used_pages                      # pool has holes
+    assert np.all(w.layout.refcounts[w.layout.block_tables[0, :64]] == 8)
+    check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
+
+
+def test_page_permutation_and_private_prefix_copies_are_bit_identical():
+    lens = [700, 1300, 64 + 5]
+    lay, q, k, v = build(8, lens, 8, 2, 128, prompt=64, slack=1.0, poison=False)
+    a = run_gpu(q, k, v, lay.block_tables, lay.seq_lens)
+    perm = wl.rng_for(8, 9).permutation(lay.NP)
+    k2 = np.empty_like(k); v2 = np.empty_like(v)
+    k2[perm] = k; v2[perm] = v
+    bt2 = np.where(lay.block_tables >= 0, perm[np.maximum(lay.block_tables, 0)], -1).astype(np.int32)
+    assert np.array_equal(a, run_gpu(q, k2, v2, bt2, lay.seq_lens))
+    # private copies of the 4 prompt pages for traces 1 and 2
+    k3 = np.concatenate([k, np.zeros((8,) + k.shape[1:], np.uint16)])
+    v3 = np.concatenate([v, np.zeros((8,) + v.shape[1:], np.uint16)])
+    bt3 = lay.block_tables.copy(); nxt = lay.NP
+    for i in (1, 2):
+        for j in range(4):
+            k3[nxt] = k[lay.block_tables[i, j]]; v3[nxt] = v[lay.block_tables[i, j]]
+            bt3[i, j] = nxt; nxt += 1
+    assert np.array_equal(a, run_gpu(q, k3, v3, bt3, lay.seq_lens))
+
+
+def test_large_logits_and_dominant_key():
+    lens = [300, 900, 40]
+    lay, q, k, v = build(9, lens, 8, 2, 128, qstd=6.0)          # logits ~ N(0, 6^2): running max moves a lot
+    check(q, k, v, lay.block_tables, lay.seq_lens)
+    qf = wl.bf16_bits_to_f32(q)
+    k[lay.block_tables[1, 20], 0, 3] = wl.f32_to_bf16_bits(8.0 * qf[1, 0])
+    got, want = check(q, k, v, lay.block_tables, lay.seq_lens, scale=1.0)
+    np.testing.assert_allclose(got[1, 0], wl.bf16_bits_to_f32(v)[lay.block_tables[1, 20], 0, 3], atol=1e-6)
+
+
+def test_all_equal_keys_give_mean_of_v():
+    lay, q, k, v = build(10, [777, 16, 3], 4, 1, 64, poison=False)
+    k[:] = k[0, 0, 0]
+    check(q, k, v, lay.block_tables, lay.seq_lens)
+
+
+def test_device_reported_errors():
+    lay, q, k, v = build(11, [100, 200], 4, 1, 64, poison=False)
+    bt = lay.block_tables.copy(); bt[1, 2] = lay.NP
+    run_gpu(q, k, v, bt, lay.seq_lens, expect_status=16)          # STEP_EPAGE
+    bt[1, 2] = -1
+    run_gpu(q, k, v, bt, lay.seq_lens, expect_status=16)
+    sl = lay.seq_lens.copy(); sl[0] = lay.MAXB * P + 1
+    run_gpu(q, k, v, lay.block_tables, sl, expect_status=17)      # STEP_ELEN
+    sl[0] = -5
+    run_gpu(q, k, v, lay.block_tables, sl, expect_status=17)
+    # garbage in unused block-table entries is ignored
+    bt = lay.block_tables.copy(); bt[0, 7:] = 123456789
+    got = run_gpu(q, k, v, bt, lay.seq_lens)
+    assert np.array_equal(got, run_gpu(q, k, v, lay.block_tables, lay.seq_lens))
+
+
+def test_host_reported_errors():
+    lay, q, k, v = build(12, [100], 4, 1, 64, poison=False)
+    tq, tk, tv, tb, tl = dev_bits(q), dev_bits(k), dev_bits(v), dev(lay.block_tables), dev(lay.seq_lens)
+    with pytest.raises(binding.StepError) as e:                   # workspace too small
+        binding.paged_decode_attn(tq, tk, tv, tb, tl, workspace=torch.zeros(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == 2
+    bad = torch.zeros(1, 4, 96, dtype=torch.int16, device=DEV)    # head_dim 96 unsupported
+    kb = torch.zeros(2, 1, 16, 96, dtype=torch.int16, device=DEV)
+    with pytest.raises(binding.StepError) as e:
+        binding.paged_decode_attn(bad, kb, kb, tb, tl, workspace=torch.zeros(1 << 20, dtype=torch.uint8, device=DEV))
+    assert e.value.code == 1
+    # N = 0 is a valid no-op
+    binding.paged_decode_attn(tq[:0], tk, tv, tb[:0], tl[:0])
+    torch.cuda.synchronize()
+
+
+def test_full_config2():
+    w = wl.make_workload(2)
+    check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
+
+
+def _device_kv(NP, Hkv, D, seed):
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    k = torch.randn((NP, Hkv, P, D), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((NP, Hkv, P, D), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    return k, v
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_full_size_sampled_rows(cfg):
+    """Configs 3 and 5 at full size, in the launch configuration bench.py times: K/V are drawn on
+    the device, a sample of (trace, head) rows is recomputed by the oracle from the bytes it reads
+    back, and every row is checked for finiteness and for staying inside the value range."""
+    w = wl.make_workload(cfg, kv=False)
+    lay, s = w.layout, w.shape
+    k, v = _device_kv(lay.NP, s.Hkv, s.D, w.seed)
+    st = new_status()
+    tq = dev_bits(w.q)
+    out = binding.paged_decode_attn(tq, k, v, dev(lay.block_tables), dev(lay.seq_lens), status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    got = host_f32_of_bf16(out)
+    assert np.all(np.isfinite(got))
+    assert np.abs(got).max() < 6.0                                 # convex combination of N(0,1) bf16 values
+    # sample: shortest, longest and two more traces; one query head per KV head; remap their pages
+    order = np.argsort(lay.seq_lens)
+    traces = np.unique([order[0], order[-1], order[len(order) // 2], order[1]])
+    heads = np.arange(s.Hkv) * (s.Hq // s.Hkv) + (np.arange(s.Hkv) % (s.Hq // s.Hkv))
+    pages = np.unique(np.concatenate([lay.block_tables[t][: (lay.seq_lens[t] + P - 1) // P] for t in traces]))
+    remap = -np.ones(lay.NP, np.int64); remap[pages] = np.arange(pages.size)
+    idx = torch.from_numpy(pages).to(DEV)
+    ks = host_bits(k.index_select(0, idx)); vs = host_bits(v.index_select(0, idx))
+    bt = np.where(lay.block_tables[traces] >= 0, remap[np.maximum(lay.block_tables[traces], 0)], -1).astype(np.int32)
+    sl = lay.seq_lens[traces].copy()
+    rows = (np.repeat(np.arange(traces.size), heads.size).astype(np.int32), np.tile(heads, traces.size).astype(np.int32))
+    want = oracle.paged_decode_attn(np.ascontiguousarray(w.q[traces]), ks, vs, bt, sl, rows=rows)
+    sel = got[traces][rows[0], rows[1]]
+    err = np.abs(sel - want)
+    assert err.max() <= TOL
+    assert np.all(err <= 2.0 ** -8 * np.abs(want) + 2e-3), float(err.max())

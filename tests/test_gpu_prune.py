@@ -1,0 +1,133 @@
+"""GPU parity of prune_free against the oracle: pruned list, freed-page list, refcounts, block
+tables and lengths must be bit-identical on identical score bytes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_09093_amd import binding, workloads as wl
+from tests.gpu_util import DEV, dev, new_status
+
+pytestmark = pytest.mark.gpu
+P = 16
+
+
+def run_gpu(scores, k, rc, bt, sl, expect_status=0):
+    st = new_status()
+    t_rc, t_bt, t_sl = dev(rc.copy()), dev(bt.copy()), dev(sl.copy())
+    pruned, freed, nf = binding.prune_free(dev(scores), k, t_rc, t_bt, t_sl, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == expect_status, binding.ERROR_NAMES.get(int(st.item()))
+    n = int(nf.item())
+    return pruned.cpu().numpy()[:k], freed.cpu().numpy()[:n], t_rc.cpu().numpy(), t_bt.cpu().numpy(), t_sl.cpu().numpy()
+
+
+def check(scores, k, lay):
+    got = run_gpu(scores, k, lay.refcounts, lay.block_tables, lay.seq_lens)
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    pruned, freed = oracle.prune_free(scores, k, rc, bt, sl, P)
+    for name, a, b in zip(("pruned", "freed", "refcounts", "block_tables", "seq_lens"), got, (pruned, freed, rc, bt, sl)):
+        assert a.dtype == b.dtype and np.array_equal(a, b), name
+    return got
+
+
+def _layout(seed, N, prompt, lo, hi, slack=1.2):
+    lens = wl.rng_for(seed, 0).integers(lo, hi + 1, N)
+    return wl.build_layout(lens, prompt, P, wl.rng_for(seed, 1), slack=slack)
+
+
+def test_config1_bottom_one_of_four():
+    w = wl.make_workload(1, kv=False)
+    scores = np.array([0.6, 0.2, 0.9, 0.4], np.float32)
+    pruned, freed, rc, *_ = check(scores, 1, w.layout)
+    assert pruned.tolist() == [1] and np.all(rc[w.layout.block_tables[0, :4]] == 3)
+
+
+def test_hand_cases_from_golden_file():
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "bottomk_hand.json")))
+    for c in g["cases"]:
+        scores = np.array([float(x) for x in c["scores"]], np.float32)
+        live = np.array(c["live"])
+        lens = np.where(live == 1, 20 + np.arange(scores.size), 0)
+        lay = wl.build_layout(lens, 0, P, wl.rng_for(1, 1))
+        pruned, *_ = check(scores, c["k"], lay)
+        assert pruned.tolist() == c["pruned"]
+
+
+@pytest.mark.parametrize("N,k", [(1, 1), (2, 1), (5, 0), (5, 5), (63, 17), (64, 64), (65, 3), (256, 64), (1000, 333),
+                                 (4096, 1024)])
+def test_sizes_with_ties_and_dead_traces(N, k):
+    lay = _layout(300 + N, N, 32, 33, 400)
+    r = wl.rng_for(300 + N, 2)
+    scores = (r.integers(0, max(N // 3, 2), N) / 64.0).astype(np.float32)      # many ties
+    scores[r.integers(0, N, max(N // 10, 1))] = np.inf                          # unscored traces
+    dead = r.integers(0, N, N // 8)
+    for t in dead:                                                              # kill some traces consistently
+        if lay.seq_lens[t] > 0:
+            pages = lay.block_tables[t][lay.block_tables[t] >= 0]
+            lay.refcounts[pages] -= 1
+            lay.block_tables[t] = -1
+            lay.seq_lens[t] = 0
+    scores[dead[: dead.size // 2]] = np.nan                                     # NaN on dead traces is ignored
+    k = min(k, int((lay.seq_lens > 0).sum()))
+    check(scores, k, lay)
+
+
+def test_scaled_down_config5_saturated_pool():
+    w = wl.make_workload(5, kv=False, N=32, tail=(1100, 3000))
+    assert w.layout.NP == w.layout.used_pages and w.prune_k == 8
+    scores = wl.rng_for(5, 3).uniform(0.2, 0.8, 32).astype(np.float32)
+    pruned, freed, rc, bt, sl = check(scores, 8, w.layout)
+    assert np.all(rc[w.layout.block_tables[0, :64]] == 24)                      # prompt pages 32 -> 24
+
+
+def test_full_config5_prune_quarter():
+    w = wl.make_workload(5, kv=False)
+    s = w.scorer
+    scores = (s.score_sum / s.score_cnt).astype(np.float32)
+    pruned, freed, rc, bt, sl = check(scores, 64, w.layout)
+    assert np.all(rc[w.layout.block_tables[0, :64]] == 192) and freed.size > 20000
+
+
+def test_two_rounds_equal_one_round_on_device():
+    lay = _layout(41, 40, 64, 65, 700)
+    scores = wl.rng_for(41, 2).uniform(0, 1, 40).astype(np.float32)
+    one = run_gpu(scores, 9, lay.refcounts, lay.block_tables, lay.seq_lens)
+    a = run_gpu(scores, 4, lay.refcounts, lay.block_tables, lay.seq_lens)
+    b = run_gpu(scores, 5, a[2], a[3], a[4])
+    assert np.concatenate([a[0], b[0]]).tolist() == one[0].tolist()
+    assert sorted(np.concatenate([a[1], b[1]]).tolist()) == one[1].tolist()
+    for x, y in zip(b[2:], one[2:]):
+        assert np.array_equal(x, y)
+
+
+def test_device_reported_errors_leave_selection_state_untouched():
+    lay = _layout(42, 8, 32, 33, 200)
+    scores = wl.rng_for(42, 2).uniform(0, 1, 8).astype(np.float32)
+    bad = scores.copy(); bad[3] = np.nan
+    got = run_gpu(bad, 2, lay.refcounts, lay.block_tables, lay.seq_lens, expect_status=19)      # STEP_ENAN
+    assert got[1].size == 0 and np.array_equal(got[2], lay.refcounts) and np.array_equal(got[3], lay.block_tables)
+    sl = lay.seq_lens.copy(); sl[:6] = 0
+    got = run_gpu(scores, 3, lay.refcounts, lay.block_tables, sl, expect_status=21)             # STEP_EKLIVE
+    assert np.array_equal(got[4], sl) and np.array_equal(got[2], lay.refcounts)
+    sl = lay.seq_lens.copy(); sl[1] = lay.MAXB * P + 1
+    run_gpu(scores, 1, lay.refcounts, lay.block_tables, sl, expect_status=17)                   # STEP_ELEN
+    t = int(np.argmin(scores))
+    bt = lay.block_tables.copy(); bt[t, 1] = lay.NP
+    run_gpu(scores, 1, lay.refcounts, bt, lay.seq_lens, expect_status=16)                       # STEP_EPAGE
+    rc = lay.refcounts.copy(); rc[lay.block_tables[t, 3]] = 0
+    got = run_gpu(scores, 1, rc, lay.block_tables, lay.seq_lens, expect_status=20)              # STEP_EREFCOUNT
+    assert got[2][lay.block_tables[t, 3]] == 0                                                  # not driven negative
+
+
+def test_host_reported_errors():
+    lay = _layout(43, 4, 0, 20, 60)
+    scores = dev(np.zeros(4, np.float32))
+    with pytest.raises(binding.StepError) as e:
+        binding.prune_free(scores, 5, dev(lay.refcounts), dev(lay.block_tables), dev(lay.seq_lens))   # k > N
+    assert e.value.code == 1
+    with pytest.raises(binding.StepError) as e:
+        binding.prune_free(scores, 1, dev(lay.refcounts), dev(lay.block_tables), dev(lay.seq_lens),
+                           workspace=torch.zeros(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == 2
