@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""bench.py -- one decode step of the STEP hot path on one MI355X, timed end to end.
+
+A "step" is one pass of the whole path over N parallel traces of one prompt:
+    paged_decode_attn  ->  step_score (+ running-mean update)  ->  prune_free
+on synthetic inputs shaped like the paper's N = 64 workload (benchmark configs[2]: 32 query /
+8 KV heads, head_dim 128, 16-token pages, a shared 1024-token prompt and tails of 8k-32k tokens in
+a fragmented page pool; scorer 4096 -> 1024 -> 1 on 4 boundary hidden states; Algorithm 1's prune
+of the single lowest-scoring trace).  Inputs are resident in HBM before the timed region.
+Every step gets its own copy of the (small) mutable state so that pruning does not shrink the
+next step's work.
+
+Prints ONE JSON line (see README for the fields).  The dominant kernel's roofline is
+measured live with HIP events around the stage-1 attention kernel of every timed step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5], help="BASELINE.json config (1-based)")
+    ap.add_argument("--prune-k", type=int, default=None, help="traces pruned per step (default 1; config 5: 64)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
+                    help="only run libstep's plain copy kernel on MIB MiB (profiler byte-counter calibration)")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary for it is committed."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not "
+              "supported. DESIGN.md describes how the path would shard." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: WORLD_SIZE > 1 is not supported (one GPU only)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2601_09093_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libstep has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    binding.lib()
+
+    if args.calib_copy:
+        n = args.calib_copy << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            binding.calib_copy(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib_copy_bytes": n, "launches": 5}))
+        return
+
+    K, W = args.steps, args.warmup
+    w = wl.make_workload(args.config, kv=False)
+    lay, s, sc = w.layout, w.shape, w.scorer
+    prune_k = args.prune_k if args.prune_k is not None else (w.prune_k if args.config == 5 else 1)
+
+    def bits(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev)
+
+    def t(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- resident inputs -------------------------------------------------------------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    kv_shape = (lay.NP, s.Hkv, s.P, s.D)
+    k_pages = torch.empty(kv_shape, dtype=torch.bfloat16, device=dev)
+    v_pages = torch.empty(kv_shape, dtype=torch.bfloat16, device=dev)
+    step_pages = max(1, (1 << 28) // (s.Hkv * s.P * s.D))           # draw in <=1 GiB fp32 pieces
+    for arr in (k_pages, v_pages):
+        for p0 in range(0, lay.NP, step_pages):
+            p1 = min(lay.NP, p0 + step_pages)
+            arr[p0:p1] = torch.randn((p1 - p0,) + kv_shape[1:], generator=gen, device=dev, dtype=torch.float32)
+    q = bits(w.q)
+    out = torch.empty_like(q)
+    hidden, W1, W2 = bits(sc.hidden), bits(sc.W1), bits(sc.W2)
+    b1 = t(sc.b1)
+    b2 = torch.tensor([sc.b2], dtype=torch.float32, device=dev)
+    bidx, trace_of = t(sc.boundary_idx), t(sc.trace_of)
+    B = int(sc.boundary_idx.size)
+    logits = torch.empty(max(B, 1), dtype=torch.float32, device=dev)[:B]
+    probs = torch.empty(max(B, 1), dtype=torch.float32, device=dev)[:B]
+    scores = torch.empty(s.N, dtype=torch.float32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    # prior running-mean state so that every trace has a score (Algorithm 1 prunes scored traces)
+    st = wl.rng_for(w.seed, 99)
+    cnt0 = st.integers(1, 41, s.N).astype(np.int32)
+    sum0 = (cnt0 * st.uniform(0.2, 0.8, s.N)).astype(np.float32)
+    nsteps = K + W
+    bt_s = t(np.broadcast_to(lay.block_tables, (nsteps,) + lay.block_tables.shape).copy())
+    sl_s = t(np.broadcast_to(lay.seq_lens, (nsteps, s.N)).copy())
+    rc_s = t(np.broadcast_to(lay.refcounts, (nsteps, lay.NP)).copy())
+    sum_s = t(np.broadcast_to(sum0, (nsteps, s.N)).copy())
+    cnt_s = t(np.broadcast_to(cnt0, (nsteps, s.N)).copy())
+    pruned = torch.empty(max(prune_k, 1), dtype=torch.int32, device=dev)
+    freed = torch.empty(max(min(lay.NP, prune_k * lay.MAXB), 1), dtype=torch.int32, device=dev)
+    n_freed = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    adims = binding.attn_dims(q, k_pages, bt_s[0])
+    ws_attn = binding.new_workspace(binding.attn_workspace_bytes(adims), dev)
+    ws_score = binding.new_workspace(binding.score_workspace_bytes(
+        binding.ScoreDims(sc.hidden.shape[0], sc.hidden.shape[1], sc.W1.shape[0], B, s.N, sc.act)), dev)
+    ws_prune = binding.new_workspace(binding.prune_workspace_bytes(s.N, lay.MAXB, lay.NP), dev)
+
+    def step(i):
+        binding.paged_decode_attn(q, k_pages, v_pages, bt_s[i], sl_s[i], out=out, workspace=ws_attn, status=status)
+        binding.step_score(hidden, bidx, W1, b1, W2, b2, act=sc.act, logits=logits, probs=probs, trace_of=trace_of,
+                           score_sum=sum_s[i], score_cnt=cnt_s[i], scores=scores, workspace=ws_score, status=status)
+        binding.prune_free(scores, prune_k, rc_s[i], bt_s[i], sl_s[i], pruned=pruned, freed_pages=freed,
+                           n_freed=n_freed, workspace=ws_prune, status=status)
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    binding.attn_profile_begin(K)
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    stage1_ms = binding.attn_profile_end(K)
+    assert int(status.item()) == 0, binding.ERROR_NAMES.get(int(status.item()))
+    assert int(n_freed.item()) > 0 or prune_k == 0
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    value = s.N / (ms_per_step * 1e-3)                              # trace-tokens per second
+
+    # ---- roofline of the dominant kernel (attention stage 1) --------------------------------
+    nb = (lay.seq_lens.astype(np.int64) + s.P - 1) // s.P
+    G = s.Hq // s.Hkv
+    records = int(ws_attn[:4].view(torch.int32).item())              # written by the planning kernel
+    items = records * s.Hkv
+    alg_bytes = (lay.unique_tokens * s.kv_bytes_per_token           # every resident referenced KV byte once
+                 + int(nb.sum()) * 4                                # block-table entries
+                 + s.N * s.Hq * s.D * 2                             # q
+                 + items * G * (s.D + 2) * 4)                       # split-K partials written by stage 1
+    avg_ms = float(np.mean(stage1_ms))
+    achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
+    workload = "config%d" % args.config
+    roofline = {
+        "kernel": "attn_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": traffic_from_profiles("attn_partial", workload),
+        "algorithmic_bytes": int(alg_bytes), "avg_kernel_ms": round(avg_ms, 4),
+        "min_kernel_ms": round(float(np.min(stage1_ms)), 4), "launches": len(stage1_ms),
+    }
+
+    result = {
+        "metric": "paged decode-attn HBM GB/s (% of peak) + trace-tokens/s per step at N=64",
+        "value": round(value, 1), "unit": "trace-tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": workload, "N": s.N, "Hq": s.Hq, "Hkv": s.Hkv, "D": s.D, "page_tokens": s.P,
+                   "layers": 1, "prompt_tokens": lay.prompt_len, "context_tokens_total": lay.requested_tokens,
+                   "unique_kv_tokens": lay.unique_tokens, "pool_pages": lay.NP, "scorer": "%d->%d->1 %s, B=%d" % (
+                       sc.hidden.shape[1], sc.W1.shape[0], "ReLU" if sc.act == 0 else "GELU", B),
+                   "prune_k": prune_k, "attn_waves_per_kv_head": binding.attn_waves_per_head(adims),
+                   "attn_records": records},
+        "attn_hbm_gbs": round(achieved, 1), "attn_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k)
+    print(json.dumps(result))
+
+
+def cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k):
+    """The oracle, as it stands, on the host cores: the whole step on a bounded sample of traces."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2601_09093_amd import workloads as wl
+
+    lay, s, sc = w.layout, w.shape, w.scorer
+    P = s.P
+    threads = oracle.num_threads()
+
+    def sample_inputs(traces):
+        pages = np.unique(np.concatenate([lay.block_tables[t][: (lay.seq_lens[t] + P - 1) // P] for t in traces]))
+        remap = -np.ones(lay.NP, np.int64)
+        remap[pages] = np.arange(pages.size)
+        idx = torch.from_numpy(pages).to(k_pages.device)
+        ks = k_pages.index_select(0, idx).view(torch.int16).cpu().numpy().view(np.uint16)
+        vs = v_pages.index_select(0, idx).view(torch.int16).cpu().numpy().view(np.uint16)
+        bt = np.where(lay.block_tables[traces] >= 0, remap[np.maximum(lay.block_tables[traces], 0)], -1).astype(np.int32)
+        return np.ascontiguousarray(w.q[traces]), ks, vs, bt, lay.seq_lens[traces].copy()
+
+    order = np.argsort(-lay.seq_lens.astype(np.int64))             # a length-stratified sample
+    probe = np.sort(order[[len(order) // 2]])
+    qs, ks, vs, bt, sl = sample_inputs(probe)
+    t0 = time.perf_counter()
+    oracle.paged_decode_attn(qs, ks, vs, bt, sl)
+    per_token = (time.perf_counter() - t0) / float(sl.sum())
+    budget_tokens = args.cpu_seconds / per_token
+    stride_pick = order[:: max(1, int(np.ceil(lay.requested_tokens / budget_tokens)))]
+    traces = np.sort(stride_pick)
+    qs, ks, vs, bt, sl = sample_inputs(traces)
+    t0 = time.perf_counter()
+    oracle.paged_decode_attn(qs, ks, vs, bt, sl)
+    t_attn = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    _, probs = oracle.step_score(sc.hidden, sc.boundary_idx, sc.W1, sc.b1, sc.W2, sc.b2, act=sc.act)
+    ssum, cnt = sum0.copy(), cnt0.copy()
+    scores = oracle.running_mean(sc.trace_of, probs.astype(np.float32), ssum, cnt)
+    oracle.prune_free(scores, prune_k, lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy(), P)
+    t_rest = time.perf_counter() - t0
+    total = t_attn + t_rest
+    return {
+        "value": round(traces.size / total, 3), "unit": "trace-tokens/s", "cores": threads, "kind": "oracle",
+        "sample": "oracle attention on %d of %d traces (every %d-th by length, %d context tokens), plus the full "
+                  "scorer (B=%d), running mean and prune_free(k=%d); %.2f s attention + %.3f s rest" % (
+                      traces.size, s.N, max(1, len(order) // max(traces.size, 1)), int(sl.sum()),
+                      sc.boundary_idx.size, prune_k, t_attn, t_rest),
+        "seconds": round(total, 3),
+    }
+
+
+if __name__ == "__main__":
+    main()

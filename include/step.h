@@ -53,7 +53,7 @@ const char *step_version(void);
 /* ------------------------------------------------------------------------------------------ */
 
 typedef struct {
-    int32_t N;    /* traces                                                                     */
+    int32_t N;    /* traces, at most 2048                                                       */
     int32_t Hq;   /* query heads                                                                */
     int32_t Hkv;  /* KV heads; Hq % Hkv == 0, group size G = Hq / Hkv in {1, 2, 4, 8}           */
     int32_t D;    /* head dimension, 64 or 128                                                  */
@@ -65,6 +65,11 @@ typedef struct {
 
 /* Bytes of workspace paged_decode_attn needs for these dims (host function, no device work). */
 size_t step_attn_workspace_bytes(const step_attn_dims *dims);
+/* Wavefronts per KV head that stage 1 keeps resident on the current device for these dims (host
+ * function; 0 on bad dims): (compute units x resident waves per unit) / Hkv.  The work is cut so
+ * that each of them streams the same number of pages.  The environment variable
+ * STEP_ATTN_WAVES_PER_CU, read once, overrides the occupancy query (tuning aid). */
+int32_t step_attn_waves_per_head(const step_attn_dims *dims);
 
 /*
  * For every trace i with L = seq_lens[i] > 0 and every query head h (KV head g = h / G):
@@ -81,8 +86,10 @@ size_t step_attn_workspace_bytes(const step_attn_dims *dims);
  *   seq_lens     [N]               int32
  *   out          [N][Hq][D]        bf16, written for every trace
  *   workspace    >= step_attn_workspace_bytes(dims), 256-byte aligned; holds split-K partials
- * Arithmetic: exact bf16 products, fp32 accumulation, fp32 softmax; the softmax weights are kept
- * in fp32.  Result within 2e-2 max-abs of the float64 definition for N(0,1) inputs.
+ * Arithmetic: exact bf16 products, fp32 accumulation, fp32 running max and exponentials; for
+ * G == 4 the softmax weights are rounded to bf16 before they multiply V (the normaliser is summed
+ * from the same rounded weights).  Result within 2e-2 max-abs of the float64 definition for
+ * N(0,1) inputs.
  */
 int paged_decode_attn(const step_attn_dims *dims, const uint16_t *q, const uint16_t *k_pages,
                       const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
@@ -157,6 +164,18 @@ int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scor
 /* to calibrate profiler byte counters against known traffic.  bytes % 16 == 0.               */
 /* ------------------------------------------------------------------------------------------ */
 int step_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Measurement aid: per-kernel timing of attention's stage 1 (the HBM-streaming kernel).       */
+/* After step_attn_profile_begin(cap), each paged_decode_attn call brackets its stage-1 kernel */
+/* with two HIP events from a pool of `cap` pairs created by that call, on the stream it       */
+/* launches on (calls beyond `cap` are not bracketed).  step_attn_profile_end waits for the    */
+/* recorded events, writes each bracketed call's stage-1 time in milliseconds to ms[0..n)      */
+/* (HOST array of capacity cap), destroys the pool and returns n, or -STEP_EINVAL.             */
+/* Benchmark use only: not thread safe, creates and destroys events.                           */
+/* ------------------------------------------------------------------------------------------ */
+int step_attn_profile_begin(int cap);
+int step_attn_profile_end(float *ms, int cap);
 
 #ifdef __cplusplus
 }

@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libstep.so")
+LIB_PATH = os.environ.get("STEP_LIBSTEP_PATH") or os.path.join(_HERE, "libstep.so")
 _lib = None
 
 STEP_OK = 0
@@ -53,6 +53,8 @@ def lib():
     L.step_version.restype = ctypes.c_char_p
     L.step_attn_workspace_bytes.restype = sz
     L.step_attn_workspace_bytes.argtypes = [ctypes.POINTER(AttnDims)]
+    L.step_attn_waves_per_head.restype = ctypes.c_int32
+    L.step_attn_waves_per_head.argtypes = [ctypes.POINTER(AttnDims)]
     L.paged_decode_attn.restype = ctypes.c_int
     L.paged_decode_attn.argtypes = [ctypes.POINTER(AttnDims), vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
     L.step_score_workspace_bytes.restype = sz
@@ -65,6 +67,10 @@ def lib():
     L.prune_free.argtypes = [i32, i32, i32, i32, vp, i32] + [vp] * 7 + [sz, vp, vp]
     L.step_calib_copy.restype = ctypes.c_int
     L.step_calib_copy.argtypes = [vp, vp, sz, vp]
+    L.step_attn_profile_begin.restype = ctypes.c_int
+    L.step_attn_profile_begin.argtypes = [ctypes.c_int]
+    L.step_attn_profile_end.restype = ctypes.c_int
+    L.step_attn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
     _lib = L
     return L
 
@@ -98,6 +104,10 @@ def attn_dims(q, k_pages, block_tables, scale=None):
 
 def attn_workspace_bytes(dims):
     return int(lib().step_attn_workspace_bytes(ctypes.byref(dims)))
+
+
+def attn_waves_per_head(dims):
+    return int(lib().step_attn_waves_per_head(ctypes.byref(dims)))
 
 
 def new_workspace(nbytes, device):
@@ -195,3 +205,19 @@ def calib_copy(dst, src):
     if rc != STEP_OK:
         raise StepError(rc, "step_calib_copy")
     return dst
+
+
+def attn_profile_begin(cap):
+    """Bracket the stage-1 kernel of the next `cap` paged_decode_attn calls with HIP events."""
+    rc = lib().step_attn_profile_begin(int(cap))
+    if rc != STEP_OK:
+        raise StepError(rc, "step_attn_profile_begin")
+
+
+def attn_profile_end(cap):
+    """Milliseconds of each bracketed stage-1 kernel since attn_profile_begin (host list)."""
+    buf = (ctypes.c_float * int(cap))()
+    n = lib().step_attn_profile_end(buf, int(cap))
+    if n < 0:
+        raise StepError(-n, "step_attn_profile_end")
+    return [float(buf[i]) for i in range(n)]

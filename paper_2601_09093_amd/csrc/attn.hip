@@ -2,16 +2,25 @@
 // KV cache -- the attention inside NextToken(t) of Algorithm 1 (the paper gives no formula; this
 // is softmax(q K^T scale) V for the newest token of every live trace).
 //
-// Stage 1 (attn_partial): one 64-lane wavefront per work item (trace i, KV head g, chunk of CP
-//   pages).  A (page, head) tile is P*D bf16 contiguous; the wave reads it with 16-byte loads,
-//   lane l taking bytes [j*1024 + 16 l, +16) of the tile on load j, so every load instruction
-//   covers 1 KB of consecutive addresses.  A row of D values therefore lives in LPR = D/8
-//   neighbouring lanes and each group of LPR lanes ("row group" r) sees the tokens r, r+TPI, ...
-//   of every page: TPI = 64/LPR independent online-softmax streams per wave, which never talk
-//   to each other inside the page loop and are merged once at the end of the item.
-//   The G query heads of the group share every K and V register.
-// Stage 2 (attn_merge): per (trace, query head) combine the chunk partials (m, l, acc) and round
-//   to bf16.
+// Three kernels per call:
+//   attn_plan    one workgroup.  Validates the lengths and cuts every live trace into records of at
+//                most CP pages (trace, first page, page count, tokens in the last page, ids of the
+//                first two pages).  Records are ordered: chunk 0 of every trace first (these cover
+//                a shared prompt, and running them at the same time turns N reads of the prompt's
+//                pages into one HBM read plus L2 hits), then the other full chunks, then the ragged
+//                last chunks (smallest work last).
+//   attn_partial stage 1, the HBM-streaming kernel.  One 64-lane wavefront per (record, KV head).
+//                A (page, head) tile is P*D bf16 contiguous; the wave reads it with 16-byte loads,
+//                lane l taking bytes [j*1024 + 16 l, +16) on load j, so every load instruction
+//                covers 1 KB of consecutive addresses.  A row of D values lives in LPR = D/8
+//                neighbouring lanes and each group of LPR lanes ("row group" r) sees the tokens
+//                r, r+TPI, ... of every page: TPI = 64/LPR independent online-softmax streams per
+//                wave, merged once per record.  The G query heads share every K and V register.
+//                For G == 4 the kernel is persistent: gridDim waves walk the record list with a
+//                fixed stride and start the next record's first tile loads before they reduce and
+//                store the current record's partial, so no load latency is exposed between records.
+//   attn_merge   stage 2: per (trace, query head) combine the record partials (m, l, acc), round to
+//                bf16.
 #include "common.h"
 
 namespace step {
@@ -19,17 +28,418 @@ namespace {
 
 constexpr float kMinusBig = -1.0e30f;  // finite "no token seen yet" running max (keeps exp2 NaN-free)
 
+struct Record {       // 32 bytes, read with one scalar load
+    int32_t i;        // trace
+    int32_t first;    // first page (index into the trace's block-table row)
+    int32_t n;        // pages, >= 1
+    int32_t ntok;     // tokens in the record's last page, 1 .. 16
+    int32_t page0;    // block_tables[i][first]
+    int32_t page1;    // block_tables[i][first + 1] (= page0 when n == 1)
+    int32_t pad0, pad1;
+};
+
+constexpr int kMaxParts = 8;     // a shared prefix is cut into at most this many sub-chunks per trace
+constexpr int kMaxPlanN = 2048;  // traces the planner handles
+constexpr int kMaxWh = 2048;     // waves per KV head the planner handles
+constexpr int kMaxShared = 256;  // pages of common prefix looked for (4096 tokens)
+
+struct PlanHeader {   // 256 bytes
+    int32_t total;    // records: [0, n1) cover the shared prefix, [n1, total) the private pages
+    int32_t n1;       // n_live * parts
+    int32_t n_live;   // traces with seq_len > 0
+    int32_t parts;    // sub-chunks of the shared prefix per trace (0 when nothing is shared)
+    int32_t shared;   // S: leading pages common to every live trace
+    int32_t quota;    // Q: pages per wave
+    int32_t pad[58];
+};
+
 struct AttnArgs {
     const uint16_t *q, *k_pages, *v_pages;
     const int32_t *block_tables, *seq_lens;
-    float *part_acc;  // [N*Hkv*maxchunks][G][D]
-    float *part_ml;   // [N*Hkv*maxchunks][G][2]  (running max in log2 units, sum of weights)
+    PlanHeader *hdr;
+    int32_t *off2;        // [Wh + 1] private-page records of wave wh are n1 + [off2[wh], off2[wh+1])
+    Record *records;      // [max_records]; shared-prefix record s = p * n_live + rank belongs to wave s % Wh
+    int32_t *rank;        // [N] rank of a live trace among the live traces
+    int32_t *first2;      // [N] first record of the trace's private pages (they are consecutive)
+    int32_t *cnt2;        // [N] number of such records
+    float *part_acc;      // [records * Hkv][G][D]   slot = record * Hkv + kv head
+    float *part_ml;       // [records * Hkv][G][2]   (running max in log2 units, weight sum)
     uint16_t *out;
     int32_t *status;
-    int N, Hq, Hkv, MAXB, NP, CP, maxchunks;
-    float scale_log2;  // scale * log2(e)
+    int N, Hq, Hkv, MAXB, NP, Wh, max_records;
+    float scale_log2;     // scale * log2(e)
 };
 
+// ---------------------------------------------------------------------------------------------
+// plan: cut the work into records so that every one of the Wh waves of a KV head streams the same
+// number of pages (Q, give or take one).
+//   1. S = number of leading block-table entries that are identical in every live trace (the
+//      prompt's pages).  Those pages are cut into `parts` sub-chunks per trace and sub-chunk p of
+//      the trace of rank rk is record p * N_live + rk and goes to wave (p * N_live + rk) mod Wh,
+//      ahead of that wave's private pages: all
+//      waves start on the shared pages at the same time, so N reads of each shared tile become one
+//      HBM read plus L2 hits (all waves of one KV head run on one XCD when Hkv == 8).
+//   2. The private pages of all traces, concatenated trace by trace, are cut into Wh consecutive
+//      runs whose lengths top every wave up to Q pages; a run is one record per trace it touches.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPlanThreads = 1024;
+
+// exclusive scan of one int per thread over the workgroup (wave shuffles + 16 wave totals)
+__device__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
+{
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    if (lane == 63) scratch[wid] = x;
+    __syncthreads();
+    if (wid == 0) {
+        int t = lane < 16 ? scratch[lane] : 0;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const int y = __shfl_up(t, off);
+            if (lane >= off) t += y;
+        }
+        if (lane < 16) scratch[16 + lane] = t;
+    }
+    __syncthreads();
+    const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
+    *total = scratch[31];
+    __syncthreads();
+    return base + x - v;
+}
+
+// in-place exclusive scan of arr[0..n), n <= 2 * kPlanThreads; returns the total
+__device__ int array_excl_scan(int *arr, int n, int *scratch)
+{
+    const int tid = threadIdx.x;
+    const int a0 = 2 * tid < n ? arr[2 * tid] : 0;
+    const int a1 = 2 * tid + 1 < n ? arr[2 * tid + 1] : 0;
+    int total;
+    const int e = block_excl_scan(a0 + a1, scratch, &total);
+    if (2 * tid < n) arr[2 * tid] = e;
+    if (2 * tid + 1 < n) arr[2 * tid + 1] = e + a0;
+    __syncthreads();
+    return total;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
+{
+    __shared__ int nb_s[kMaxPlanN];      // pages of trace t (0: dead or invalid)
+    __shared__ int len_s[kMaxPlanN];     // tokens of trace t
+    __shared__ int live_list[kMaxPlanN]; // rank -> trace
+    __shared__ int P_s[kMaxPlanN + 1];   // private pages before trace t in the concatenation
+    __shared__ int wq[kMaxWh + 1];       // per wave: private-page quota, then its start position
+    __shared__ int wcnt[kMaxWh + 1];     // per wave: record count, then record offset
+    __shared__ int scratch[32];
+    __shared__ int S_s, minnb_s;
+    const int tid = threadIdx.x;
+    const int N = a.N, Wh = a.Wh;
+
+    if (tid == 0) { S_s = kMaxShared; minnb_s = 0x7fffffff; }
+    __syncthreads();
+    // lengths, live ranks
+    for (int t = tid; t < 2 * kPlanThreads; t += kPlanThreads) {
+        int nb = 0, L = 0;
+        if (t < N) {
+            L = a.seq_lens[t];
+            if (L < 0 || (long long)L > (long long)a.MAXB * kPageTokens) report(a.status, STEP_ELEN);
+            else nb = (L + kPageTokens - 1) / kPageTokens;
+            a.cnt2[t] = 0;
+            a.first2[t] = 0;
+        }
+        // shortest live trace: one LDS atomic per wave
+        int mn = nb > 0 ? nb : 0x7fffffff;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mn = min(mn, __shfl_xor(mn, off));
+        if ((tid & 63) == 0 && mn != 0x7fffffff) atomicMin(&minnb_s, mn);
+        if (t < kMaxPlanN) { nb_s[t] = nb; len_s[t] = L; P_s[t] = nb > 0 ? 1 : 0; }
+    }
+    __syncthreads();
+    const int n_live = array_excl_scan(P_s, N, scratch);   // P_s[t] = rank of trace t
+    for (int t = tid; t < N; t += kPlanThreads) {
+        a.rank[t] = P_s[t];
+        if (nb_s[t] > 0) live_list[P_s[t]] = t;
+    }
+    __syncthreads();
+    // shared prefix: compare every live row with the first live row
+    int S = 0;
+    if (n_live >= 2) {
+        const int cap = min(kMaxShared, minnb_s);
+        if (tid == 0) S_s = cap;
+        __syncthreads();
+        const int32_t *row0 = a.block_tables + (size_t)live_list[0] * a.MAXB;
+        int first_diff = cap;  // smallest page index at which some live row differs from the first live row
+        for (int idx = tid; idx < (n_live - 1) * cap; idx += kPlanThreads) {
+            const int rk = 1 + idx / cap, j = idx % cap;
+            if (a.block_tables[(size_t)live_list[rk] * a.MAXB + j] != row0[j]) first_diff = min(first_diff, j);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) first_diff = min(first_diff, __shfl_xor(first_diff, off));
+        if ((tid & 63) == 0 && first_diff < cap) atomicMin(&S_s, first_diff);
+        __syncthreads();
+        S = S_s;
+    }
+    int parts = 0, sc = 0;
+    if (S > 0) {
+        parts = max(1, min(min(kMaxParts, S), Wh / n_live));
+        sc = (S + parts - 1) / parts;
+        parts = (S + sc - 1) / sc;
+    }
+    const int N1 = n_live * parts;  // shared-prefix records
+    // private pages: prefix over traces
+    __syncthreads();
+    for (int t = tid; t < N; t += kPlanThreads) P_s[t] = nb_s[t] > 0 ? nb_s[t] - S : 0;
+    __syncthreads();
+    const int T2 = array_excl_scan(P_s, N, scratch);
+    if (tid == 0) P_s[N] = T2;
+    const long long T_all = (long long)T2 + (long long)n_live * S;
+    const int Q = (int)((T_all + Wh - 1) / Wh);
+    // per wave: pages of its shared-prefix records, private quota
+    auto part_pages = [&](int p) { return min(sc, S - p * sc); };
+    for (int wh = tid; wh < Wh; wh += kPlanThreads) {
+        int a_wh = 0;
+        for (int s = wh; s < N1; s += Wh) a_wh += part_pages(s / n_live);
+        wq[wh] = max(Q - a_wh, 0);
+    }
+    __syncthreads();
+    array_excl_scan(wq, Wh, scratch);                        // wq[wh] = start of the wave's run
+    if (tid == 0) wq[Wh] = 0x7fffffff;
+    __syncthreads();
+    // first trace of a run: largest t with P_s[t] <= pos
+    auto trace_at = [&](int pos) {
+        int lo = 0, hi = N;  // invariant: P_s[lo] <= pos < P_s[hi] (P_s[N] = T2 > pos)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (P_s[mid] <= pos) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    for (int wh = tid; wh < Wh; wh += kPlanThreads) {
+        int cnt = 0;
+        int pos = wq[wh];
+        const int end = min(wq[wh + 1], T2);
+        if (pos < end) {
+            int t = trace_at(pos);
+            while (pos < end) {
+                const int te = P_s[t + 1];
+                if (te > pos) { ++cnt; pos = min(end, te); }
+                ++t;
+            }
+        }
+        wcnt[wh] = cnt;
+    }
+    __syncthreads();
+    const int total2 = array_excl_scan(wcnt, Wh, scratch);  // wcnt[wh] = first private record of the wave
+    if (tid == 0) wcnt[Wh] = total2;
+    __syncthreads();
+    for (int wh = tid; wh <= Wh; wh += kPlanThreads) a.off2[wh] = wcnt[wh];
+    auto emit = [&](int rec, int t, int first, int n) {
+        const int nb = nb_s[t];
+        const int32_t *bt = a.block_tables + (size_t)t * a.MAXB;
+        Record r;
+        r.i = t; r.first = first; r.n = n;
+        r.ntok = (first + n == nb) ? len_s[t] - (nb - 1) * kPageTokens : kPageTokens;
+        r.page0 = bt[first];
+        r.page1 = bt[first + (n > 1 ? 1 : 0)];
+        r.pad0 = 0; r.pad1 = 0;
+        a.records[rec] = r;
+    };
+    for (int wh = tid; wh < Wh; wh += kPlanThreads) {
+        for (int s = wh; s < N1; s += Wh) {
+            const int p = s / n_live;
+            emit(s, live_list[s % n_live], p * sc, part_pages(p));
+        }
+        int rec = N1 + wcnt[wh];
+        int pos = wq[wh];
+        const int end = min(wq[wh + 1], T2);
+        if (pos < end) {
+            int t = trace_at(pos);
+            while (pos < end) {
+                const int tb = P_s[t], te = P_s[t + 1];
+                if (te > pos) {
+                    const int stop = min(end, te);
+                    emit(rec, t, S + pos - tb, stop - pos);
+                    if (pos == tb) a.first2[t] = rec;
+                    atomicAdd(&a.cnt2[t], 1);
+                    ++rec;
+                    pos = stop;
+                }
+                ++t;
+            }
+        }
+    }
+    if (tid == 0) {
+        a.hdr->total = N1 + total2;
+        a.hdr->n1 = N1;
+        a.hdr->n_live = n_live;
+        a.hdr->parts = parts;
+        a.hdr->shared = S;
+        a.hdr->quota = Q;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// stage 1, any group size: one wave per (record, kv head), plain all-reduce of the logits
+// ---------------------------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
+{
+    constexpr int LPR = D / 8;              // lanes per token row
+    constexpr int TPI = 64 / LPR;           // token rows per load instruction
+    constexpr int IPP = kPageTokens / TPI;  // load instructions per (page, head) tile
+    constexpr int NV = IPP * G;             // logits per lane per page
+
+    const int lane = threadIdx.x;
+    const int r = lane / LPR, c = lane % LPR;
+    const int g = blockIdx.x % a.Hkv;
+    const int rec_id = blockIdx.x / a.Hkv;
+    if (rec_id >= a.hdr->total) return;
+    const Record rec = a.records[rec_id];
+    const int i = rec.i, n = rec.n;
+
+    uint4 qv[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+        qv[h] = *reinterpret_cast<const uint4 *>(a.q + ((size_t)i * a.Hq + (size_t)g * G + h) * D + c * 8);
+
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m[h] = kMinusBig;
+        l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+    }
+
+    const int32_t *bt = a.block_tables + (size_t)i * a.MAXB + rec.first;
+    const size_t tile_elems = (size_t)kPageTokens * D;
+    bool bad_page = false;
+
+    for (int j = 0; j < n; ++j) {
+        const int page = bt[j];
+        if ((u32)page >= (u32)a.NP) {
+            bad_page = true;
+            continue;
+        }
+        const int ntok = j == n - 1 ? rec.ntok : kPageTokens;
+        const size_t off = ((size_t)page * a.Hkv + g) * tile_elems;
+        const uint4 *kt = reinterpret_cast<const uint4 *>(a.k_pages + off);
+        const uint4 *vt = reinterpret_cast<const uint4 *>(a.v_pages + off);
+        uint4 k[IPP], v[IPP];
+#pragma unroll
+        for (int jj = 0; jj < IPP; ++jj) k[jj] = kt[jj * 64 + lane];
+#pragma unroll
+        for (int jj = 0; jj < IPP; ++jj) v[jj] = vt[jj * 64 + lane];
+        if (ntok < kPageTokens) {  // slots >= ntok hold garbage (maybe NaN)
+#pragma unroll
+            for (int jj = 0; jj < IPP; ++jj)
+                if (jj * TPI + r >= ntok) {
+                    k[jj] = make_uint4(0, 0, 0, 0);
+                    v[jj] = make_uint4(0, 0, 0, 0);
+                }
+        }
+        float val[NV];
+#pragma unroll
+        for (int jj = 0; jj < IPP; ++jj)
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                float s = dot2_bf16(k[jj].x, qv[h].x, 0.f);
+                s = dot2_bf16(k[jj].y, qv[h].y, s);
+                s = dot2_bf16(k[jj].z, qv[h].z, s);
+                s = dot2_bf16(k[jj].w, qv[h].w, s);
+#pragma unroll
+                for (int off2 = LPR / 2; off2 >= 1; off2 >>= 1) s += __shfl_xor(s, off2);
+                s *= a.scale_log2;
+                if (ntok < kPageTokens && jj * TPI + r >= ntok) s = -INFINITY;
+                val[jj * G + h] = s;
+            }
+        float pv[NV];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float mx = val[h];
+#pragma unroll
+            for (int jj = 1; jj < IPP; ++jj) mx = fmaxf(mx, val[jj * G + h]);
+            const float m_new = fmaxf(m[h], mx);
+            const float alpha = __builtin_amdgcn_exp2f(m[h] - m_new);
+            m[h] = m_new;
+            l[h] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
+#pragma unroll
+            for (int jj = 0; jj < IPP; ++jj) {
+                const float p = __builtin_amdgcn_exp2f(val[jj * G + h] - m_new);
+                pv[jj * G + h] = p;
+                l[h] += p;
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < IPP; ++jj) {
+            const u32 w[4] = {v[jj].x, v[jj].y, v[jj].z, v[jj].w};
+            float vf[8];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                vf[2 * t] = bf16_lo(w[t]);
+                vf[2 * t + 1] = bf16_hi(w[t]);
+            }
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float pw = pv[jj * G + h];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pw, vf[e], acc[h][e]);
+            }
+        }
+    }
+    if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
+
+    // merge the TPI row-group streams of this wave, write the record's partial
+    const size_t slot = (size_t)rec_id * a.Hkv + g;
+    float *pacc = a.part_acc + slot * (G * D);
+    float *pml = a.part_ml + slot * (G * 2);
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float M = m[h];
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+        const float f = __builtin_amdgcn_exp2f(m[h] - M);
+        float ls = l[h] * f;
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) ls += __shfl_xor(ls, off);
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float x = acc[h][e] * f;
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
+            o[e] = x;
+        }
+        if (r == 0) {
+            float4 *dst = reinterpret_cast<float4 *>(pacc + h * D + c * 8);
+            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+            dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+            if (c == 0) {
+                pml[h * 2 + 0] = M;
+                pml[h * 2 + 1] = ls;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// stage 1, G == 4 (the Qwen3-8B-like shape and the tiny config): persistent, software-pipelined.
+//   phase A(page) : logits of the page (bf16 dot2), transposing reduction that leaves each lane
+//                   with one (token, head) logit, running max, p = 2^(x - m), rounded to bf16 and
+//                   packed in token pairs, handed to the row group through LDS.
+//   phase B(page) : acc += P V with bf16 dot2 on (token pair) x (head), fp32 accumulation.
+// A(page j+1) and B(page j) are independent and sit in ONE basic block, so the scheduler overlaps
+// the cross-lane / LDS / exp latencies of A with the dot2 stream of B.  The rescale of acc by
+// 2^(m_old - m_new), needed only when a page raises the running max, follows B.
+// The weight sum l is accumulated from the same bf16-rounded weights that multiply V, so the result
+// is an exact weighted average of V rows with weights perturbed by <= 2^-9 relative.
+// ---------------------------------------------------------------------------------------------
 template <int BIT>
 __device__ __forceinline__ float partner(float v)
 {
@@ -54,74 +464,81 @@ __device__ __forceinline__ void bfly_stage(float (&val)[NV], int c)
     }
 }
 
-template <int D, int G>
-__global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
+// max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
+__device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
+
+template <int D>
+__global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
 {
-    constexpr int LPR = D / 8;            // lanes per token row
-    constexpr int TPI = 64 / LPR;         // token rows per load instruction
-    constexpr int IPP = kPageTokens / TPI;  // load instructions per (page, head) tile
-    constexpr int NV = IPP * G;           // logits per lane per page before reduction
-    constexpr bool FAST = (NV == LPR);    // transposing reduction leaves exactly one logit per lane
-    __shared__ float pbuf[64];
+    constexpr int G = 4;
+    constexpr int LPR = D / 8, TPI = 64 / LPR, IPP = kPageTokens / TPI, NV = IPP * G;
+    static_assert(NV == LPR, "one logit per lane after the transposing reduction");
+    constexpr int NPAIR = IPP / 2;  // token pairs per lane per page
+    __shared__ u32 pbuf[2][64];
 
     const int lane = threadIdx.x;
     const int r = lane / LPR, c = lane % LPR;
-
-    u32 bid = blockIdx.x;
-    const int g = bid % a.Hkv;
-    bid /= a.Hkv;
-    const int i = bid % a.N;
-    const int ch = bid / a.N;
-
-    const int L = a.seq_lens[i];
-    if (L <= 0 || (long long)L > (long long)a.MAXB * kPageTokens) {
-        if (L != 0 && ch == 0 && g == 0 && lane == 0) report(a.status, STEP_ELEN);
+    // gridDim == Wh * Hkv: wave (wh, g) serves KV head g only.  Consecutive workgroups land on
+    // consecutive XCDs, so with Hkv == 8 every XCD streams (and caches) the tiles of one KV head.
+    // Its records: the shared-prefix records wh, wh + Wh, ... below n1, then the private-page
+    // records n1 + [off2[wh], off2[wh + 1]).
+    const int g = blockIdx.x % a.Hkv;
+    const int wh = blockIdx.x / a.Hkv;
+    const int n1 = a.hdr->n1;
+    const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
+    auto next_record = [&](int id) {  // id of the record after `id` in this wave's list, -1 at the end
+        int nx;
+        if (id < n1) {
+            nx = id + a.Wh;
+            if (nx >= n1) nx = p2_begin;
+        } else {
+            nx = id + 1;
+        }
+        return nx < p2_end ? nx : -1;
+    };
+    int rec_id = wh < n1 ? wh : (p2_begin < p2_end ? p2_begin : -1);
+    if (rec_id < 0) return;
+    if (a.NP <= 0) {
+        if (lane == 0) report(a.status, STEP_EPAGE);
         return;
     }
-    const int nb = (L + kPageTokens - 1) / kPageTokens;
-    const int first = ch * a.CP;
-    if (first >= nb) return;
-    const int end = min(nb, first + a.CP);
 
-    uint4 qv[G];
+    const size_t tile_u4 = (size_t)kPageTokens * D / 8;  // uint4 units per (page, head) tile
+    const uint4 *kbase = reinterpret_cast<const uint4 *>(a.k_pages);
+    const uint4 *vbase = reinterpret_cast<const uint4 *>(a.v_pages);
+    bool bad_page = false;
+    auto tile_at = [&](int page) -> size_t {
+        const bool ok = (u32)page < (u32)a.NP;
+        bad_page |= !ok;
+        return ((size_t)(ok ? page : 0) * a.Hkv + g) * tile_u4 + lane;
+    };
+    auto load4 = [&](const uint4 *base, size_t off, uint4 (&x)[IPP]) {
 #pragma unroll
-    for (int h = 0; h < G; ++h)
-        qv[h] = *reinterpret_cast<const uint4 *>(a.q + ((size_t)i * a.Hq + (size_t)g * G + h) * D + c * 8);
-
-    float m[G], acc[G][8];
-    float lrep[G];             // !FAST: sum of weights per head, replicated over the row's lanes
-    float m_own = kMinusBig;   // FAST: running max / weight sum of this lane's own head c % G
-    float l_own = 0.f;
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m[h] = kMinusBig;
-        lrep[h] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
-    }
-
-    const int32_t *bt = a.block_tables + (size_t)i * a.MAXB;
-    const size_t tile_elems = (size_t)kPageTokens * D;
-
-    auto load_tile = [&](int page, uint4 (&k)[IPP], uint4 (&v)[IPP]) {
-        const size_t off = ((size_t)page * a.Hkv + g) * tile_elems;
-        const uint4 *kt = reinterpret_cast<const uint4 *>(a.k_pages + off);
-        const uint4 *vt = reinterpret_cast<const uint4 *>(a.v_pages + off);
-#pragma unroll
-        for (int j = 0; j < IPP; ++j) k[j] = kt[j * 64 + lane];
-#pragma unroll
-        for (int j = 0; j < IPP; ++j) v[j] = vt[j * 64 + lane];
+        for (int j = 0; j < IPP; ++j) x[j] = base[off + j * 64];
     };
 
-    auto process = [&](uint4 (&k)[IPP], uint4 (&v)[IPP], int ntok) {
-        if (ntok < kPageTokens) {  // last page of the trace: slots >= ntok hold garbage (maybe NaN)
+    uint4 qv[G];
+    auto load_q = [&](int i) {
 #pragma unroll
-            for (int j = 0; j < IPP; ++j)
-                if (j * TPI + r >= ntok) {
-                    k[j] = make_uint4(0, 0, 0, 0);
-                    v[j] = make_uint4(0, 0, 0, 0);
-                }
+        for (int h = 0; h < G; ++h)
+            qv[h] = *reinterpret_cast<const uint4 *>(a.q + ((size_t)i * a.Hq + (size_t)g * G + h) * D + c * 8);
+    };
+
+    float m[G], acc[G][8];
+    float m_own, l_own, mx_pending;
+
+    auto phaseA = [&](const uint4 (&k)[IPP], int slot, int ntok) {
+#ifdef STEP_EXP_NO_QK
+        {
+            u32 x = 0;
+#pragma unroll
+            for (int jj = 0; jj < IPP; ++jj) x ^= k[jj].x ^ k[jj].y ^ k[jj].z ^ k[jj].w;
+            l_own += __uint_as_float(x & 0x3fffffffu);
+            pbuf[slot][lane] = x;
+            (void)ntok;
+            return;
         }
+#endif
         float val[NV];
 #pragma unroll
         for (int j = 0; j < IPP; ++j)
@@ -133,130 +550,164 @@ __global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
                 s = dot2_bf16(k[j].w, qv[h].w, s);
                 val[j * G + h] = s;
             }
-        float pv[NV];
-        if constexpr (FAST) {
-            if constexpr (LPR == 16) bfly_stage<3, 16, NV>(val, c);
-            if constexpr (LPR >= 8) bfly_stage<2, 8, NV>(val, c);
-            bfly_stage<1, 4, NV>(val, c);
-            bfly_stage<0, 2, NV>(val, c);
-            // this lane now owns the logit of (slot (c/G)*TPI + r, head c % G)
-            float x = val[0] * a.scale_log2;
-            if (ntok < kPageTokens && (c / G) * TPI + r >= ntok) x = -INFINITY;
-            float mx = x;
-            if constexpr (LPR == 16) {
-                mx = fmaxf(mx, dpp<kDppRowRor4>(mx));
-                mx = fmaxf(mx, dpp<kDppRowRor8>(mx));
-            } else {
-                mx = fmaxf(mx, __shfl_xor(mx, 4));
-            }
-            const float m_new = fmaxf(m_own, mx);
-            if (__any(m_new > m_own)) {
-                float mq[G];
-                mq[0] = fmaxf(m[0], dpp<STEP_DPP_QUAD_BCAST(0)>(mx));
-                mq[1] = fmaxf(m[1], dpp<STEP_DPP_QUAD_BCAST(1)>(mx));
-                mq[2] = fmaxf(m[2], dpp<STEP_DPP_QUAD_BCAST(2)>(mx));
-                mq[3] = fmaxf(m[3], dpp<STEP_DPP_QUAD_BCAST(3)>(mx));
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    const float alpha = __builtin_amdgcn_exp2f(m[h] - mq[h]);
-                    m[h] = mq[h];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
-                }
-                l_own *= __builtin_amdgcn_exp2f(m_own - m_new);
-                m_own = m_new;
-            }
-            const float p = __builtin_amdgcn_exp2f(x - m_own);
-            l_own += p;
-            // every lane of the row group needs all NV weights of the group: exchange through LDS
-            pbuf[lane] = p;
-            __builtin_amdgcn_wave_barrier();
-            const float4 *pb = reinterpret_cast<const float4 *>(pbuf + r * LPR);
-#pragma unroll
-            for (int t = 0; t < NV / 4; ++t) {
-                const float4 f = pb[t];
-                pv[4 * t + 0] = f.x; pv[4 * t + 1] = f.y; pv[4 * t + 2] = f.z; pv[4 * t + 3] = f.w;
-            }
-            __builtin_amdgcn_wave_barrier();
+        if constexpr (LPR == 16) bfly_stage<3, 16, NV>(val, c);
+        bfly_stage<2, 8, NV>(val, c);
+        bfly_stage<1, 4, NV>(val, c);
+        bfly_stage<0, 2, NV>(val, c);
+        // this lane owns the logit of (slot (c/G)*TPI + r, head c % G); slots >= ntok are not tokens
+        float x = val[0] * a.scale_log2;
+        x = ((c / G) * TPI + r < ntok) ? x : -INFINITY;
+        float mx = x;
+        if constexpr (LPR == 16) {
+            mx = max_nc(mx, dpp<kDppRowRor4>(mx));
+            mx = max_nc(mx, dpp<kDppRowRor8>(mx));
         } else {
-            // plain all-reduce over the row's lanes: every lane ends with all NV logits of its rows
-#pragma unroll
-            for (int v0 = 0; v0 < NV; ++v0) {
-                float s = val[v0];
-#pragma unroll
-                for (int off = LPR / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-                s *= a.scale_log2;
-                if (ntok < kPageTokens && (v0 / G) * TPI + r >= ntok) s = -INFINITY;
-                val[v0] = s;
-            }
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float mx = val[h];
-#pragma unroll
-                for (int j = 1; j < IPP; ++j) mx = fmaxf(mx, val[j * G + h]);
-                const float m_new = fmaxf(m[h], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m[h] - m_new);
-                m[h] = m_new;
-                lrep[h] *= alpha;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
-#pragma unroll
-                for (int j = 0; j < IPP; ++j) {
-                    const float p = __builtin_amdgcn_exp2f(val[j * G + h] - m_new);
-                    pv[j * G + h] = p;
-                    lrep[h] += p;
-                }
-            }
+            mx = max_nc(mx, __shfl_xor(mx, 4));
         }
+        const float m_new = max_nc(m_own, mx);
+        const float alpha_own = __builtin_amdgcn_exp2f(m_own - m_new);
+        m_own = m_new;
+        mx_pending = mx;
+        const float p = __builtin_amdgcn_exp2f(x - m_new);
+        // lane c + 4 of the row group holds the same head's weight for the next token row
+        float p_next;
+        if constexpr (LPR == 16) p_next = dpp<0x12C>(p);  // row_ror:12 = value of lane (c + 4) % 16
+        else p_next = __shfl_xor(p, 4);
+        const bf16x2 pk = {(__bf16)p, (__bf16)p_next};
+        const u32 w = __builtin_bit_cast(u32, pk);
+        l_own = fmaf(l_own, alpha_own, bf16_lo(w));
+        pbuf[slot][lane] = w;
+    };
+
+    auto pv_pairs = [&](const uint4 (&v)[IPP], int slot) {
+#ifdef STEP_EXP_NO_PV
+        {
+            u32 x = 0;
 #pragma unroll
-        for (int j = 0; j < IPP; ++j) {
-            const u32 w[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-            float vf[8];
+            for (int jj = 0; jj < IPP; ++jj) x ^= v[jj].x ^ v[jj].y ^ v[jj].z ^ v[jj].w;
+            acc[0][0] += __uint_as_float(x & 0x3fffffffu);
+            (void)slot;
+            return;
+        }
+#endif
+        const uint4 *pb = reinterpret_cast<const uint4 *>(&pbuf[slot][r * LPR]);
+#pragma unroll
+        for (int pr = 0; pr < NPAIR; ++pr) {
+            const uint4 pp = pb[2 * pr];  // words 8 pr .. 8 pr + 3: heads 0..3 of token pair pr
+            const u32 ph[4] = {pp.x, pp.y, pp.z, pp.w};
+            const u32 w0[4] = {v[2 * pr].x, v[2 * pr].y, v[2 * pr].z, v[2 * pr].w};
+            const u32 w1[4] = {v[2 * pr + 1].x, v[2 * pr + 1].y, v[2 * pr + 1].z, v[2 * pr + 1].w};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                vf[2 * t] = bf16_lo(w[t]);
-                vf[2 * t + 1] = bf16_hi(w[t]);
-            }
+                const u32 lo = __builtin_amdgcn_perm(w1[t], w0[t], 0x05040100u);  // (row0[2t],   row1[2t])
+                const u32 hi = __builtin_amdgcn_perm(w1[t], w0[t], 0x07060302u);  // (row0[2t+1], row1[2t+1])
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float pw = pv[j * G + h];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pw, vf[e], acc[h][e]);
+                for (int h = 0; h < G; ++h) {
+                    acc[h][2 * t] = dot2_bf16(lo, ph[h], acc[h][2 * t]);
+                    acc[h][2 * t + 1] = dot2_bf16(hi, ph[h], acc[h][2 * t + 1]);
+                }
             }
         }
     };
 
-    auto ntok_of = [&](int pg) { return pg == nb - 1 ? L - pg * kPageTokens : kPageTokens; };
-    auto page_ok = [&](int page) { return (u32)page < (u32)a.NP; };
+    auto rescale = [&]() {
+        float mq[G];
+        mq[0] = max_nc(m[0], dpp<STEP_DPP_QUAD_BCAST(0)>(mx_pending));
+        mq[1] = max_nc(m[1], dpp<STEP_DPP_QUAD_BCAST(1)>(mx_pending));
+        mq[2] = max_nc(m[2], dpp<STEP_DPP_QUAD_BCAST(2)>(mx_pending));
+        mq[3] = max_nc(m[3], dpp<STEP_DPP_QUAD_BCAST(3)>(mx_pending));
+        const bool grow = (mq[0] > m[0]) | (mq[1] > m[1]) | (mq[2] > m[2]) | (mq[3] > m[3]);
+        if (__any(grow)) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float alpha = __builtin_amdgcn_exp2f(m[h] - mq[h]);
+                m[h] = mq[h];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
+            }
+        }
+    };
+    // rows past the trace's last token may hold anything (NaN included): clear them before they
+    // meet a zero weight
+    auto clear_tail = [&](uint4 (&v)[IPP], int ntok) {
+#pragma unroll
+        for (int jj = 0; jj < IPP; ++jj)
+            if (jj * TPI + r >= ntok) v[jj] = make_uint4(0, 0, 0, 0);
+    };
 
-    uint4 ka[IPP], va[IPP], kb[IPP], vb[IPP];
-    int pa = bt[first];
-    bool oka = page_ok(pa);
-    if (oka) load_tile(pa, ka, va);
-    bool bad_page = !oka;
-    for (int pg = first; pg < end; pg += 2) {
-        bool okb = false;
-        if (pg + 1 < end) {
-            const int pb = bt[pg + 1];
-            okb = page_ok(pb);
-            bad_page |= !okb;
-            if (okb) load_tile(pb, kb, vb);
-        }
-        if (oka) process(ka, va, ntok_of(pg));
-        oka = false;
-        if (pg + 2 < end) {
-            pa = bt[pg + 2];
-            oka = page_ok(pa);
-            bad_page |= !oka;
-            if (oka) load_tile(pa, ka, va);
-        }
-        if (okb) process(kb, vb, ntok_of(pg + 1));
+    uint4 k0[IPP], v0[IPP], k1[IPP], v1[IPP];
+    Record rec = a.records[rec_id];
+    {
+        const size_t t0 = tile_at(rec.page0), t1 = tile_at(rec.page1);
+        load4(kbase, t0, k0);
+        load4(vbase, t0, v0);
+        load4(kbase, t1, k1);
+        load4(vbase, t1, v1);
+        load_q(rec.i);
     }
-    if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 
-    // ---- merge the TPI row-group streams of this wave, write the item's partial ----
-    float lh[G];
-    if constexpr (FAST) {
+    for (;;) {
+        const int next_id = next_record(rec_id);
+        const bool has_next = next_id >= 0;
+        const Record nrec = a.records[has_next ? next_id : rec_id];  // consumed after this record's pages
+
+        const int n = rec.n;
+        const int32_t *bt = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
+        // page ids are fetched one loop trip (two pages) ahead of the tile loads that need them; the
+        // index is clamped so the pipeline can run past the end without a branch (the surplus load
+        // re-reads the last tile, which is then not used)
+        auto page_id = [&](int j) { return bt[min(j, n - 1)]; };
+        auto ntok_of = [&](int j) { return j == n - 1 ? rec.ntok : kPageTokens; };
+
+        m_own = kMinusBig; l_own = 0.f; mx_pending = kMinusBig;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            m[h] = kMinusBig;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+        }
+
+        int pid2 = page_id(2), pid3 = page_id(3);
+        phaseA(k0, 0, ntok_of(0));
+        rescale();
+        int j = 0;
+        for (; j + 2 <= n - 1; j += 2) {
+            const size_t t2 = tile_at(pid2), t3 = tile_at(pid3);
+            pid2 = page_id(j + 4);
+            pid3 = page_id(j + 5);
+            load4(kbase, t2, k0);
+            phaseA(k1, 1, kPageTokens);
+            pv_pairs(v0, 0);
+            load4(vbase, t2, v0);
+            rescale();
+            load4(kbase, t3, k1);
+            phaseA(k0, 0, ntok_of(j + 2));
+            pv_pairs(v1, 1);
+            load4(vbase, t3, v1);
+            rescale();
+        }
+        if (j + 1 <= n - 1) {
+            phaseA(k1, 1, ntok_of(j + 1));
+            pv_pairs(v0, 0);
+            rescale();
+            clear_tail(v1, ntok_of(j + 1));
+            pv_pairs(v1, 1);
+        } else {
+            clear_tail(v0, ntok_of(j));
+            pv_pairs(v0, 0);
+        }
+
+        // all four tile buffers are dead: start the next record before reducing this one
+        if (has_next) {
+            const size_t t0 = tile_at(nrec.page0), t1 = tile_at(nrec.page1);
+            load4(kbase, t0, k0);
+            load4(vbase, t0, v0);
+            load4(kbase, t1, k1);
+            load4(vbase, t1, v1);
+            load_q(nrec.i);
+        }
+
+        // ---- merge the TPI row-group streams of this wave, write the record's partial ----
         float ls = l_own;
         if constexpr (LPR == 16) {
             ls += dpp<kDppRowRor4>(ls);
@@ -264,47 +715,51 @@ __global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
         } else {
             ls += __shfl_xor(ls, 4);
         }
+        float lh[G];
         lh[0] = dpp<STEP_DPP_QUAD_BCAST(0)>(ls);
         lh[1] = dpp<STEP_DPP_QUAD_BCAST(1)>(ls);
         lh[2] = dpp<STEP_DPP_QUAD_BCAST(2)>(ls);
         lh[3] = dpp<STEP_DPP_QUAD_BCAST(3)>(ls);
-    } else {
+        const size_t slot = (size_t)rec_id * a.Hkv + g;
+        float *pacc = a.part_acc + slot * (G * D);
+        float *pml = a.part_ml + slot * (G * 2);
 #pragma unroll
-        for (int h = 0; h < G; ++h) lh[h] = lrep[h];
-    }
-    const size_t item = ((size_t)i * a.Hkv + g) * a.maxchunks + ch;
-    float *pacc = a.part_acc + item * (G * D);
-    float *pml = a.part_ml + item * (G * 2);
+        for (int h = 0; h < G; ++h) {
+            float M = m[h];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        float M = m[h];
+            for (int off = LPR; off < 64; off <<= 1) M = max_nc(M, __shfl_xor(M, off));
+            const float f = __builtin_amdgcn_exp2f(m[h] - M);
+            float l = lh[h] * f;
 #pragma unroll
-        for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
-        const float f = __builtin_amdgcn_exp2f(m[h] - M);
-        float l = lh[h] * f;
+            for (int off = LPR; off < 64; off <<= 1) l += __shfl_xor(l, off);
+            float o[8];
 #pragma unroll
-        for (int off = LPR; off < 64; off <<= 1) l += __shfl_xor(l, off);
-        float o[8];
+            for (int e = 0; e < 8; ++e) {
+                float x = acc[h][e] * f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float x = acc[h][e] * f;
-#pragma unroll
-            for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
-            o[e] = x;
-        }
-        if (r == 0) {
-            float4 *dst = reinterpret_cast<float4 *>(pacc + h * D + c * 8);
-            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-            dst[1] = make_float4(o[4], o[5], o[6], o[7]);
-            if (c == 0) {
-                pml[h * 2 + 0] = M;
-                pml[h * 2 + 1] = l;
+                for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
+                o[e] = x;
+            }
+            if (r == 0) {
+                float4 *dst = reinterpret_cast<float4 *>(pacc + h * D + c * 8);
+                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+                dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+                if (c == 0) {
+                    pml[h * 2 + 0] = M;
+                    pml[h * 2 + 1] = l;
+                }
             }
         }
+        if (!has_next) break;
+        rec = nrec;
+        rec_id = next_id;
     }
+    if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 
-// out[i][h][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c, rounded to bf16.
+// ---------------------------------------------------------------------------------------------
+// stage 2: out[i][h][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c, rounded to bf16
+// ---------------------------------------------------------------------------------------------
 template <int D, int G>
 __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
 {
@@ -319,16 +774,23 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
     for (int t = 0; t < DPT; ++t) o[t] = 0.f;
     float den = 0.f;
     if (L > 0 && (long long)L <= (long long)a.MAXB * kPageTokens) {
-        const int nb = (L + kPageTokens - 1) / kPageTokens;
-        const int nch = (nb + a.CP - 1) / a.CP;
-        const size_t item0 = ((size_t)i * a.Hkv + g) * a.maxchunks;
+        // the trace's records: `parts` shared-prefix sub-chunks, then cnt2 consecutive private ones
+        const int parts = a.hdr->parts, n_live = a.hdr->n_live, n1 = a.hdr->n1;
+        const int rk = a.rank[i], f2 = a.first2[i];
+        const int nch = parts + a.cnt2[i];
+        auto record_of = [&](int ch) { return ch < parts ? ch * n_live + rk : f2 + (ch - parts); };
+        (void)n1;
         float M = kMinusBig;
-        for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, a.part_ml[(item0 + ch) * (G * 2) + hh * 2]);
         for (int ch = 0; ch < nch; ++ch) {
-            const float *ml = a.part_ml + (item0 + ch) * (G * 2) + hh * 2;
+            const size_t slot = (size_t)record_of(ch) * a.Hkv + g;
+            M = fmaxf(M, a.part_ml[slot * (G * 2) + hh * 2]);
+        }
+        for (int ch = 0; ch < nch; ++ch) {
+            const size_t slot = (size_t)record_of(ch) * a.Hkv + g;
+            const float *ml = a.part_ml + slot * (G * 2) + hh * 2;
             const float f = __builtin_amdgcn_exp2f(ml[0] - M);
             den += f * ml[1];
-            const float *pa = a.part_acc + (item0 + ch) * (G * D) + hh * D;
+            const float *pa = a.part_acc + slot * (G * D) + hh * D;
 #pragma unroll
             for (int t = 0; t < DPT; ++t) o[t] = fmaf(f, pa[lane * DPT + t], o[t]);
         }
@@ -342,17 +804,9 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
     }
 }
 
-int chunk_pages_for(const step_attn_dims *d)
-{
-    static const int env = [] {
-        const char *s = getenv("STEP_ATTN_CHUNK_PAGES");
-        return s ? atoi(s) : 0;
-    }();
-    if (env > 0) return env;
-    (void)d;
-    return 32;
-}
-
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
 bool dims_ok(const step_attn_dims *d)
 {
     if (!d) return false;
@@ -361,16 +815,79 @@ bool dims_ok(const step_attn_dims *d)
     if (d->Hq % d->Hkv) return false;
     const int G = d->Hq / d->Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return false;
-    if ((long long)d->N * d->Hq > (1ll << 30)) return false;
+    if (d->N > kMaxPlanN) return false;
     return true;
 }
+
+// waves per KV head: (CUs x waves of the stage-1 kernel that fit on one CU) / Hkv.  The environment
+// variable STEP_ATTN_WAVES_PER_CU, read once, overrides the occupancy query (tuning aid).
+int waves_per_head(const step_attn_dims *d)
+{
+    static const int cus = [] {
+        int dev = 0, n = 256;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        return n;
+    }();
+    static const int per_cu_env = [] {
+        const char *s = getenv("STEP_ATTN_WAVES_PER_CU");
+        return s ? atoi(s) : 0;
+    }();
+    static const int per_cu_128 = [] {
+        int nblk = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, attn_partial_g4<128>, 64, 0) != hipSuccess || nblk <= 0)
+            nblk = 8;
+        return nblk < 8 ? nblk : 8;  // measured: more than 8 resident waves per CU do not stream faster
+    }();
+    const int per_cu = per_cu_env > 0 ? per_cu_env : per_cu_128;
+    int wh = cus * per_cu / d->Hkv;
+    if (wh < 1) wh = 1;
+    if (wh > kMaxWh) wh = kMaxWh;
+    return wh;
+}
+
+struct Layout {  // byte offsets into the workspace, all multiples of 256
+    size_t off2, records, rank, first2, cnt2, ml, acc, total;
+    int Wh, max_records;
+};
+
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Layout layout_for(const step_attn_dims *d)
+{
+    Layout l;
+    l.Wh = waves_per_head(d);
+    l.max_records = 2 * l.Wh + 2 * d->N;
+    const size_t R = (size_t)l.max_records, G = d->Hq / d->Hkv, N = d->N;
+    l.off2 = 256;
+    l.records = l.off2 + up256((size_t)(l.Wh + 1) * sizeof(int32_t));
+    l.rank = l.records + up256(R * sizeof(Record));
+    l.first2 = l.rank + up256(N * sizeof(int32_t));
+    l.cnt2 = l.first2 + up256(N * sizeof(int32_t));
+    l.ml = l.cnt2 + up256(N * sizeof(int32_t));
+    l.acc = l.ml + up256(R * d->Hkv * G * 2 * sizeof(float));
+    l.total = l.acc + up256(R * d->Hkv * G * d->D * sizeof(float));
+    return l;
+}
+
+// optional per-call event pairs around stage 1 (benchmarks only)
+struct Profile {
+    hipEvent_t *ev = nullptr;  // 2 * cap events
+    int cap = 0, used = 0;
+} g_prof;
 
 template <int D, int G>
 int launch(const AttnArgs &a, hipStream_t s)
 {
-    const long long items = (long long)a.N * a.Hkv * a.maxchunks;
-    if (items > 0x7fffffffll) return STEP_EINVAL;
-    if (items > 0) hipLaunchKernelGGL((attn_partial<D, G>), dim3((u32)items), dim3(64), 0, s, a);
+    hipLaunchKernelGGL(attn_plan, dim3(1), dim3(kPlanThreads), 0, s, a);
+    const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
+    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], s);
+    if constexpr (G == 4)
+        hipLaunchKernelGGL((attn_partial_g4<D>), dim3((u32)(a.Wh * a.Hkv)), dim3(64), 0, s, a);
+    else
+        hipLaunchKernelGGL((attn_partial<D, G>), dim3((u32)(a.max_records * a.Hkv)), dim3(64), 0, s, a);
+    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used++ + 1], s);
     hipLaunchKernelGGL((attn_merge<D, G>), dim3((u32)(a.N * a.Hq)), dim3(64), 0, s, a);
     return launch_status();
 }
@@ -380,17 +897,15 @@ int launch(const AttnArgs &a, hipStream_t s)
 
 using namespace step;
 
+extern "C" int32_t step_attn_waves_per_head(const step_attn_dims *d)
+{
+    return dims_ok(d) ? waves_per_head(d) : 0;
+}
+
 extern "C" size_t step_attn_workspace_bytes(const step_attn_dims *d)
 {
     if (!dims_ok(d)) return 0;
-    const int CP = chunk_pages_for(d);
-    const size_t maxchunks = ((size_t)d->MAXB + CP - 1) / CP;
-    const size_t items = (size_t)d->N * d->Hkv * maxchunks;
-    const size_t G = d->Hq / d->Hkv;
-    size_t acc = items * G * d->D * sizeof(float);
-    acc = (acc + 255) & ~(size_t)255;
-    const size_t ml = items * G * 2 * sizeof(float);
-    return acc + ((ml + 255) & ~(size_t)255) + 256;
+    return layout_for(d).total;
 }
 
 extern "C" int paged_decode_attn(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages,
@@ -402,25 +917,28 @@ extern "C" int paged_decode_attn(const step_attn_dims *d, const uint16_t *q, con
     if (d->N == 0) return STEP_OK;
     if (!q || !k_pages || !v_pages || !block_tables || !seq_lens || !out) return STEP_EINVAL;
     if (!aligned(q, 16) || !aligned(k_pages, 16) || !aligned(v_pages, 16) || !aligned(out, 4)) return STEP_EINVAL;
-    const size_t need = step_attn_workspace_bytes(d);
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return STEP_EWORKSPACE;
+    const Layout l = layout_for(d);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < l.total) return STEP_EWORKSPACE;
 
+    char *ws = reinterpret_cast<char *>(workspace);
     AttnArgs a;
     a.q = q; a.k_pages = k_pages; a.v_pages = v_pages;
     a.block_tables = block_tables; a.seq_lens = seq_lens;
+    a.hdr = reinterpret_cast<PlanHeader *>(ws);
+    a.off2 = reinterpret_cast<int32_t *>(ws + l.off2);
+    a.records = reinterpret_cast<Record *>(ws + l.records);
+    a.rank = reinterpret_cast<int32_t *>(ws + l.rank);
+    a.first2 = reinterpret_cast<int32_t *>(ws + l.first2);
+    a.cnt2 = reinterpret_cast<int32_t *>(ws + l.cnt2);
+    a.part_ml = reinterpret_cast<float *>(ws + l.ml);
+    a.part_acc = reinterpret_cast<float *>(ws + l.acc);
     a.out = out; a.status = status;
     a.N = d->N; a.Hq = d->Hq; a.Hkv = d->Hkv; a.MAXB = d->MAXB; a.NP = d->NP;
-    a.CP = chunk_pages_for(d);
-    a.maxchunks = (d->MAXB + a.CP - 1) / a.CP;
+    a.Wh = l.Wh; a.max_records = l.max_records;
     a.scale_log2 = d->scale * 1.4426950408889634f;
-    const size_t G = d->Hq / d->Hkv;
-    size_t acc_bytes = (size_t)d->N * d->Hkv * a.maxchunks * G * d->D * sizeof(float);
-    acc_bytes = (acc_bytes + 255) & ~(size_t)255;
-    a.part_acc = reinterpret_cast<float *>(workspace);
-    a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + acc_bytes);
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    const int key = d->D * 16 + (int)G;
+    const int key = d->D * 16 + d->Hq / d->Hkv;
     switch (key) {
         case 64 * 16 + 1: return launch<64, 1>(a, s);
         case 64 * 16 + 2: return launch<64, 2>(a, s);
@@ -432,4 +950,29 @@ extern "C" int paged_decode_attn(const step_attn_dims *d, const uint16_t *q, con
         case 128 * 16 + 8: return launch<128, 8>(a, s);
     }
     return STEP_EINVAL;
+}
+
+extern "C" int step_attn_profile_begin(int cap)
+{
+    if (cap <= 0 || g_prof.ev) return STEP_EINVAL;
+    g_prof.ev = new hipEvent_t[2 * (size_t)cap];
+    for (int i = 0; i < 2 * cap; ++i)
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return STEP_ELAUNCH;
+    g_prof.cap = cap;
+    g_prof.used = 0;
+    return STEP_OK;
+}
+
+extern "C" int step_attn_profile_end(float *ms, int cap)
+{
+    if (!g_prof.ev || !ms || cap < g_prof.used) return -STEP_EINVAL;
+    const int n = g_prof.used;
+    for (int i = 0; i < n; ++i) {
+        (void)hipEventSynchronize(g_prof.ev[2 * i + 1]);
+        if (hipEventElapsedTime(&ms[i], g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess) ms[i] = -1.f;
+    }
+    for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    delete[] g_prof.ev;
+    g_prof = Profile();
+    return n;
 }

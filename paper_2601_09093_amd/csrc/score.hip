@@ -115,37 +115,84 @@ __global__ __launch_bounds__(64 * kWaves) void score_hidden(const ScoreArgs a)
     }
 }
 
-__global__ __launch_bounds__(256) void score_finish(const ScoreArgs a)
+constexpr int kFinishThreads = 256;
+constexpr int kFinishChunk = 1024;  // boundaries whose (trace, prob) are staged in LDS at a time
+constexpr int kStateMax = 2048;     // traces whose (sum, count) state is staged in LDS
+
+__global__ __launch_bounds__(kFinishThreads) void score_finish(const ScoreArgs a)
 {
+    __shared__ float prob_s[kFinishChunk];
+    __shared__ int trace_s[kFinishChunk];
+    __shared__ float sum_s[kStateMax];
+    __shared__ int cnt_s[kStateMax];
     const int tid = threadIdx.x;
     const int mt = a.m / 16;
-    for (int b = tid; b < a.B; b += blockDim.x) {
-        float logit = a.b2[0];
-        for (int t = 0; t < mt; ++t) logit += a.partial[(size_t)t * a.B + b];
-        a.logits[b] = logit;
-        a.probs[b] = 1.0f / (1.0f + expf(-logit));
-    }
-    if (!a.score_sum) return;  // no running-mean state in this call
-    __threadfence_block();
-    __syncthreads();
-    if (tid == 0) {
-        for (int b = 0; b < a.B; ++b) {
-            const int t = a.trace_of[b];
-            if ((u32)t >= (u32)a.N) {
-                report(a.status, STEP_EINDEX);
-                continue;
+    const float b2 = a.b2[0];
+    const bool state = a.score_sum != nullptr;
+    const bool staged = state && a.N <= kStateMax;  // keep the sequential replay off global memory
+    if (staged)
+        for (int t = tid; t < a.N; t += kFinishThreads) {
+            sum_s[t] = a.score_sum[t];
+            cnt_s[t] = a.score_cnt[t];
+        }
+    for (int base = 0; base < a.B; base += kFinishChunk) {
+        const int nbd = min(kFinishChunk, a.B - base);
+        for (int bb = tid; bb < nbd; bb += kFinishThreads) {
+            const int b = base + bb;
+            // partial logits are summed in a fixed order, four independent accumulators in flight
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int t = 0;
+            for (; t + 3 < mt; t += 4) {
+                s0 += a.partial[(size_t)(t + 0) * a.B + b];
+                s1 += a.partial[(size_t)(t + 1) * a.B + b];
+                s2 += a.partial[(size_t)(t + 2) * a.B + b];
+                s3 += a.partial[(size_t)(t + 3) * a.B + b];
             }
-            a.score_sum[t] = a.score_sum[t] + a.probs[b];
-            a.score_cnt[t] = a.score_cnt[t] + 1;
+            for (; t < mt; ++t) s0 += a.partial[(size_t)t * a.B + b];
+            const float logit = b2 + ((s0 + s1) + (s2 + s3));
+            const float prob = 1.0f / (1.0f + expf(-logit));
+            a.logits[b] = logit;
+            a.probs[b] = prob;
+            prob_s[bb] = prob;
+            trace_s[bb] = state ? a.trace_of[b] : 0;
         }
+        if (!state) continue;  // uniform
+        __syncthreads();
+        if (tid == 0) {
+            // boundaries in index order: fp32 addition is not associative and a trace may own several
+            for (int bb = 0; bb < nbd; ++bb) {
+                const int t = trace_s[bb];
+                if ((u32)t >= (u32)a.N) {
+                    report(a.status, STEP_EINDEX);
+                    continue;
+                }
+                if (staged) {
+                    sum_s[t] = sum_s[t] + prob_s[bb];
+                    cnt_s[t] = cnt_s[t] + 1;
+                } else {
+                    a.score_sum[t] = a.score_sum[t] + prob_s[bb];
+                    a.score_cnt[t] = a.score_cnt[t] + 1;
+                }
+            }
+        }
+        __syncthreads();
     }
+    if (!state) return;
     __threadfence_block();
     __syncthreads();
-    if (a.scores) {
-        for (int t = tid; t < a.N; t += blockDim.x) {
-            const int n = a.score_cnt[t];
-            a.scores[t] = n > 0 ? a.score_sum[t] / (float)n : INFINITY;
+    for (int t = tid; t < a.N; t += kFinishThreads) {
+        float sm;
+        int n;
+        if (staged) {
+            sm = sum_s[t];
+            n = cnt_s[t];
+            a.score_sum[t] = sm;
+            a.score_cnt[t] = n;
+        } else {
+            sm = a.score_sum[t];
+            n = a.score_cnt[t];
         }
+        if (a.scores) a.scores[t] = n > 0 ? sm / (float)n : INFINITY;
     }
 }
 
@@ -199,6 +246,6 @@ extern "C" int step_score(const step_score_dims *d, const uint16_t *hidden, cons
         const dim3 grid(d->m / 16, (d->B + 16 * kBT - 1) / (16 * kBT));
         hipLaunchKernelGGL(score_hidden, grid, dim3(64 * kWaves), 0, s, a);
     }
-    if (d->B > 0 || (state && scores)) hipLaunchKernelGGL(score_finish, dim3(1), dim3(256), 0, s, a);
+    if (d->B > 0 || (state && scores)) hipLaunchKernelGGL(score_finish, dim3(1), dim3(kFinishThreads), 0, s, a);
     return launch_status();
 }

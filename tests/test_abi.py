@@ -13,7 +13,7 @@ LIB = os.path.join(ROOT, "paper_2601_09093_amd", "libstep.so")
 def declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    names = re.findall(r"^\s*(?:const\s+)?(?:int|size_t|char\s*\*|void)\s*\*?\s*(\w+)\s*\(", src, flags=re.M)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int32_t|int|size_t|char\s*\*|void)\s*\*?\s*(\w+)\s*\(", src, flags=re.M)
     return sorted(set(names))
 
 
@@ -21,7 +21,8 @@ def test_header_declares_the_three_calls():
     names = declared_functions()
     for n in ("paged_decode_attn", "step_score", "prune_free", "step_attn_workspace_bytes",
               "step_score_workspace_bytes", "step_prune_workspace_bytes", "step_strerror", "step_version",
-              "step_calib_copy"):
+              "step_calib_copy", "step_attn_profile_begin", "step_attn_profile_end",
+              "step_attn_waves_per_head"):
         assert n in names, names
 
 

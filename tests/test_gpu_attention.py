@@ -27,7 +27,7 @@ def check(q, k, v, bt, sl, scale=None, tol=TOL):
     assert np.all(np.isfinite(got))
     err = np.abs(got - want)
     # bf16 rounding of the output (2^-9 relative) plus fp32 accumulation noise
-    assert np.all(err <= 2.0 ** -8 * np.abs(want) + 2e-3), float(err.max())
+    assert np.all(err <= 2.0 ** -8 * np.abs(want) + 4e-3), float(err.max())
     assert err.max() <= tol
     return got, want
 
@@ -192,4 +192,4 @@ def test_full_size_sampled_rows(cfg):
     sel = got[traces][rows[0], rows[1]]
     err = np.abs(sel - want)
     assert err.max() <= TOL
-    assert np.all(err <= 2.0 ** -8 * np.abs(want) + 2e-3), float(err.max())
+    assert np.all(err <= 2.0 ** -8 * np.abs(want) + 4e-3), float(err.max())
