@@ -121,7 +121,7 @@ def main():
     st = wl.rng_for(w.seed, 99)
     cnt0 = st.integers(1, 41, s.N).astype(np.int32)
     sum0 = (cnt0 * st.uniform(0.2, 0.8, s.N)).astype(np.float32)
-    nsteps = K + W
+    nsteps = 2 * K + W
     bt_s = t(np.broadcast_to(lay.block_tables, (nsteps,) + lay.block_tables.shape).copy())
     sl_s = t(np.broadcast_to(lay.seq_lens, (nsteps, s.N)).copy())
     rc_s = t(np.broadcast_to(lay.refcounts, (nsteps, lay.NP)).copy())
@@ -144,15 +144,21 @@ def main():
         binding.prune_free(scores, prune_k, rc_s[i], bt_s[i], sl_s[i], pruned=pruned, freed_pages=freed,
                            n_freed=n_freed, workspace=ws_prune, status=status)
 
+    # state copies: W warm-up steps, K timed steps, K more steps with stage 1 bracketed by events
     for i in range(W):
         step(i)
     torch.cuda.synchronize()
-    binding.attn_profile_begin(K)
     t0 = time.perf_counter()
     for i in range(W, W + K):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # the same K steps again with HIP events around the stage-1 attention kernel of every step (the
+    # event records cost a few microseconds each, so they stay out of the step time above)
+    binding.attn_profile_begin(K)
+    for i in range(W + K, W + 2 * K):
+        step(i)
+    torch.cuda.synchronize()
     stage1_ms = binding.attn_profile_end(K)
     assert int(status.item()) == 0, binding.ERROR_NAMES.get(int(status.item()))
     assert int(n_freed.item()) > 0 or prune_k == 0

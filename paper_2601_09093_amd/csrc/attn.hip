@@ -28,14 +28,11 @@ namespace {
 
 constexpr float kMinusBig = -1.0e30f;  // finite "no token seen yet" running max (keeps exp2 NaN-free)
 
-struct Record {       // 32 bytes, read with one scalar load
+struct Record {       // 16 bytes, read with one scalar load
     int32_t i;        // trace
     int32_t first;    // first page (index into the trace's block-table row)
     int32_t n;        // pages, >= 1
     int32_t ntok;     // tokens in the record's last page, 1 .. 16
-    int32_t page0;    // block_tables[i][first]
-    int32_t page1;    // block_tables[i][first + 1] (= page0 when n == 1)
-    int32_t pad0, pad1;
 };
 
 constexpr int kMaxParts = 8;     // a shared prefix is cut into at most this many sub-chunks per trace
@@ -173,9 +170,21 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         __syncthreads();
         const int32_t *row0 = a.block_tables + (size_t)live_list[0] * a.MAXB;
         int first_diff = cap;  // smallest page index at which some live row differs from the first live row
-        for (int idx = tid; idx < (n_live - 1) * cap; idx += kPlanThreads) {
-            const int rk = 1 + idx / cap, j = idx % cap;
-            if (a.block_tables[(size_t)live_list[rk] * a.MAXB + j] != row0[j]) first_diff = min(first_diff, j);
+        // consecutive lanes compare consecutive entries of one row (coalesced), four loads in flight
+        const int work = (n_live - 1) * cap;
+        for (int base = 0; base < work; base += 4 * kPlanThreads) {
+            int x[4], y[4], jj[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = min(base + u * kPlanThreads + tid, work - 1);
+                const int rk = 1 + idx / cap;
+                jj[u] = idx % cap;
+                x[u] = a.block_tables[(size_t)live_list[rk] * a.MAXB + jj[u]];
+                y[u] = row0[jj[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (x[u] != y[u]) first_diff = min(first_diff, jj[u]);
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) first_diff = min(first_diff, __shfl_xor(first_diff, off));
@@ -239,13 +248,9 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
     for (int wh = tid; wh <= Wh; wh += kPlanThreads) a.off2[wh] = wcnt[wh];
     auto emit = [&](int rec, int t, int first, int n) {
         const int nb = nb_s[t];
-        const int32_t *bt = a.block_tables + (size_t)t * a.MAXB;
         Record r;
         r.i = t; r.first = first; r.n = n;
         r.ntok = (first + n == nb) ? len_s[t] - (nb - 1) * kPageTokens : kPageTokens;
-        r.page0 = bt[first];
-        r.page1 = bt[first + (n > 1 ? 1 : 0)];
-        r.pad0 = 0; r.pad1 = 0;
         a.records[rec] = r;
     };
     for (int wh = tid; wh < Wh; wh += kPlanThreads) {
@@ -638,7 +643,8 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     uint4 k0[IPP], v0[IPP], k1[IPP], v1[IPP];
     Record rec = a.records[rec_id];
     {
-        const size_t t0 = tile_at(rec.page0), t1 = tile_at(rec.page1);
+        const int32_t *bt0 = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
+        const size_t t0 = tile_at(bt0[0]), t1 = tile_at(bt0[rec.n > 1 ? 1 : 0]);
         load4(kbase, t0, k0);
         load4(vbase, t0, v0);
         load4(kbase, t1, k1);
@@ -649,7 +655,11 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     for (;;) {
         const int next_id = next_record(rec_id);
         const bool has_next = next_id >= 0;
-        const Record nrec = a.records[has_next ? next_id : rec_id];  // consumed after this record's pages
+        // the next record and the ids of its first two pages are fetched now and consumed after this
+        // record's pages
+        const Record nrec = a.records[has_next ? next_id : rec_id];
+        const int32_t *nbt = a.block_tables + (size_t)nrec.i * a.MAXB + nrec.first;
+        const int npage0 = nbt[0], npage1 = nbt[nrec.n > 1 ? 1 : 0];
 
         const int n = rec.n;
         const int32_t *bt = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
@@ -699,7 +709,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
 
         // all four tile buffers are dead: start the next record before reducing this one
         if (has_next) {
-            const size_t t0 = tile_at(nrec.page0), t1 = tile_at(nrec.page1);
+            const size_t t0 = tile_at(npage0), t1 = tile_at(npage1);
             load4(kbase, t0, k0);
             load4(vbase, t0, v0);
             load4(kbase, t1, k1);
@@ -769,28 +779,59 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
     const int g = h / G, hh = h % G;
     uint16_t *orow = a.out + ((size_t)i * a.Hq + h) * D;
     const int L = a.seq_lens[i];
+    // the trace's records: `parts` shared-prefix sub-chunks, then cnt2 consecutive private ones
+    const int parts = a.hdr->parts, n_live = a.hdr->n_live;
+    const int rk = a.rank[i], f2 = a.first2[i];
+    int nch = parts + a.cnt2[i];
+    if (L <= 0 || (long long)L > (long long)a.MAXB * kPageTokens) nch = 0;
+    auto slot_of = [&](int ch) { return (size_t)(ch < parts ? ch * n_live + rk : f2 + (ch - parts)) * a.Hkv + g; };
+
     float o[DPT];
 #pragma unroll
     for (int t = 0; t < DPT; ++t) o[t] = 0.f;
-    float den = 0.f;
-    if (L > 0 && (long long)L <= (long long)a.MAXB * kPageTokens) {
-        // the trace's records: `parts` shared-prefix sub-chunks, then cnt2 consecutive private ones
-        const int parts = a.hdr->parts, n_live = a.hdr->n_live, n1 = a.hdr->n1;
-        const int rk = a.rank[i], f2 = a.first2[i];
-        const int nch = parts + a.cnt2[i];
-        auto record_of = [&](int ch) { return ch < parts ? ch * n_live + rk : f2 + (ch - parts); };
-        (void)n1;
-        float M = kMinusBig;
-        for (int ch = 0; ch < nch; ++ch) {
-            const size_t slot = (size_t)record_of(ch) * a.Hkv + g;
-            M = fmaxf(M, a.part_ml[slot * (G * 2) + hh * 2]);
+    float M = kMinusBig, den = 0.f;
+    // 64 pieces at a time: lane p holds (m, l) of piece base + p, the wave agrees on the maximum,
+    // then the piece accumulators are added with four loads in flight
+    for (int base = 0; base < nch; base += 64) {
+        const int cnt = min(64, nch - base);
+        float mp = kMinusBig, lp = 0.f;
+        if (lane < cnt) {
+            const float *ml = a.part_ml + slot_of(base + lane) * (G * 2) + hh * 2;
+            mp = ml[0];
+            lp = ml[1];
         }
-        for (int ch = 0; ch < nch; ++ch) {
-            const size_t slot = (size_t)record_of(ch) * a.Hkv + g;
-            const float *ml = a.part_ml + slot * (G * 2) + hh * 2;
-            const float f = __builtin_amdgcn_exp2f(ml[0] - M);
-            den += f * ml[1];
-            const float *pa = a.part_acc + slot * (G * D) + hh * D;
+        float Mn = mp;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) Mn = fmaxf(Mn, __shfl_xor(Mn, off));
+        Mn = fmaxf(Mn, M);
+        const float resc = __builtin_amdgcn_exp2f(M - Mn);
+        M = Mn;
+        den *= resc;
+#pragma unroll
+        for (int t = 0; t < DPT; ++t) o[t] *= resc;
+        const float fp = __builtin_amdgcn_exp2f(mp - M);  // 0 for lanes without a piece
+        float lsum = fp * lp;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lsum += __shfl_xor(lsum, off);
+        den += lsum;
+        int p = 0;
+        for (; p + 3 < cnt; p += 4) {
+            float v[4][DPT], f[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float *pa = a.part_acc + slot_of(base + p + u) * (G * D) + hh * D;
+                f[u] = __shfl(fp, p + u);
+#pragma unroll
+                for (int t = 0; t < DPT; ++t) v[u][t] = pa[lane * DPT + t];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int t = 0; t < DPT; ++t) o[t] = fmaf(f[u], v[u][t], o[t]);
+        }
+        for (; p < cnt; ++p) {
+            const float *pa = a.part_acc + slot_of(base + p) * (G * D) + hh * D;
+            const float f = __shfl(fp, p);
 #pragma unroll
             for (int t = 0; t < DPT; ++t) o[t] = fmaf(f, pa[lane * DPT + t], o[t]);
         }

@@ -4,12 +4,14 @@
 //
 // prune_select : one workgroup.  Builds 64-bit keys (order-preserving image of the fp32 score in
 //                the high word, trace index in the low word; dead traces get the all-ones key),
-//                sorts them with a bitonic network in LDS and writes the first k indices.  Also
+//                sorts them with a bitonic network (exchanges closer than 64 keys are wavefront
+//                shuffles, farther ones go through LDS) and writes the first k indices.  Also
 //                validates lengths and scores and clears the freed-page bitmap.
 // prune_release: one thread per (pruned trace, block-table entry): atomic decrement of the page's
 //                refcount; the decrement that reaches zero sets the page's bit in the bitmap.
 // prune_compact: one workgroup scans the bitmap in ascending page order (popcount + prefix sum)
 //                and writes the freed page ids; then marks the pruned traces dead.
+// prune_fused  : all of the above in one workgroup, for small problems.
 #include "common.h"
 
 namespace step {
@@ -80,19 +82,46 @@ __global__ __launch_bounds__(kSelThreads) void prune_select(const PruneArgs a)
         return;
     }
     // bitonic sort, ascending
-    for (int size = 2; size <= a.npad; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int t = tid; t < (a.npad >> 1); t += kSelThreads) {
-                const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
-                const int hi = lo + stride;
-                const bool asc = (lo & size) == 0;
-                const u64 x = keys[lo], y = keys[hi];
-                if ((x > y) == asc) {
-                    keys[lo] = y;
-                    keys[hi] = x;
+    if (a.npad <= kSelThreads) {
+        // one key per thread; exchanges at distance < 64 stay inside a wavefront (shuffles), larger
+        // distances go through LDS
+        u64 key = tid < a.npad ? keys[tid] : ~0ull;
+        for (int size = 2; size <= a.npad; size <<= 1) {
+            const bool asc = (tid & size) == 0;
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                u64 other;
+                if (stride >= 64) {
+                    __syncthreads();
+                    keys[tid] = key;
+                    __syncthreads();
+                    other = keys[tid ^ stride];
+                } else {
+                    const u32 lo = __shfl_xor((u32)key, stride), hi = __shfl_xor((u32)(key >> 32), stride);
+                    other = ((u64)hi << 32) | lo;
                 }
+                const bool lower = (tid & stride) == 0;       // this thread keeps the smaller key when ascending
+                const bool take_min = lower == asc;
+                key = take_min ? (key < other ? key : other) : (key > other ? key : other);
             }
-            __syncthreads();
+        }
+        __syncthreads();
+        if (tid < a.npad) keys[tid] = key;
+        __syncthreads();
+    } else {
+        for (int size = 2; size <= a.npad; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int t = tid; t < (a.npad >> 1); t += kSelThreads) {
+                    const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool asc = (lo & size) == 0;
+                    const u64 x = keys[lo], y = keys[hi];
+                    if ((x > y) == asc) {
+                        keys[lo] = y;
+                        keys[hi] = x;
+                    }
+                }
+                __syncthreads();
+            }
         }
     }
     for (int j = tid; j < a.k; j += kSelThreads) a.pruned[j] = (int32_t)(u32)keys[j];
@@ -126,9 +155,36 @@ __global__ __launch_bounds__(256) void prune_release(const PruneArgs a)
     *entry = -1;
 }
 
+// exclusive scan of one int per thread over the workgroup (wave shuffles + 16 wave totals)
+__device__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
+{
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    if (lane == 63) scratch[wid] = x;
+    __syncthreads();
+    if (wid == 0) {
+        int t = lane < 16 ? scratch[lane] : 0;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const int y = __shfl_up(t, off);
+            if (lane >= off) t += y;
+        }
+        if (lane < 16) scratch[16 + lane] = t;
+    }
+    __syncthreads();
+    const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
+    *total = scratch[31];
+    return base + x - v;
+}
+
 __global__ __launch_bounds__(kSelThreads) void prune_compact(const PruneArgs a)
 {
-    __shared__ int scan[kSelThreads];
+    __shared__ int scratch[32];
     const int tid = threadIdx.x;
     const int k_eff = a.hdr->k_eff;
     const int per = (a.words + kSelThreads - 1) / kSelThreads;
@@ -136,16 +192,9 @@ __global__ __launch_bounds__(kSelThreads) void prune_compact(const PruneArgs a)
     int cnt = 0;
     if (k_eff > 0)
         for (int wv = w0; wv < w1; ++wv) cnt += __popc(a.bitmap[wv]);
-    scan[tid] = cnt;
-    __syncthreads();
-    for (int off = 1; off < kSelThreads; off <<= 1) {  // inclusive Hillis-Steele scan
-        const int v = tid >= off ? scan[tid - off] : 0;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
-    }
-    int pos = scan[tid] - cnt;
-    if (k_eff > 0)
+    int total;
+    int pos = block_excl_scan(cnt, scratch, &total);
+    if (k_eff > 0 && cnt > 0)
         for (int wv = w0; wv < w1; ++wv) {
             u32 bits = a.bitmap[wv];
             while (bits) {
@@ -154,8 +203,129 @@ __global__ __launch_bounds__(kSelThreads) void prune_compact(const PruneArgs a)
                 a.freed_pages[pos++] = wv * 32 + b;
             }
         }
-    if (tid == kSelThreads - 1) *a.n_freed = scan[tid];
+    if (tid == 0) *a.n_freed = total;
     for (int r = tid; r < k_eff; r += kSelThreads) a.seq_lens[a.pruned[r]] = 0;
+}
+
+// Small problems (N <= 1024 traces, at most 8192 block-table entries to release, a bitmap that fits
+// LDS): the three phases above in ONE workgroup, with the keys, the lengths and the freed-page
+// bitmap in LDS, so a prune of a few traces costs one launch instead of three.
+constexpr int kFusedN = 1024;
+constexpr int kFusedWords = 8192;    // bitmap words in LDS: pools of up to 262144 pages
+constexpr int kFusedEntries = 8192;  // k * MAXB
+
+__global__ __launch_bounds__(kSelThreads) void prune_fused(const PruneArgs a)
+{
+    __shared__ u64 keys[kFusedN];
+    __shared__ int lens[kFusedN];
+    __shared__ u32 bitmap[kFusedWords];
+    __shared__ int scratch[32];
+    __shared__ int live_count, err;
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        live_count = 0;
+        err = 0;
+    }
+    for (int wv = tid; wv < a.words; wv += kSelThreads) bitmap[wv] = 0u;
+    __syncthreads();
+    {
+        u64 key = ~0ull;
+        int L = 0;
+        if (tid < a.N) {
+            L = a.seq_lens[tid];
+            if (L < 0 || (long long)L > (long long)a.MAXB * a.P) {
+                atomicCAS(&err, 0, (int)STEP_ELEN);
+            } else if (L > 0) {
+                const float s = a.scores[tid];
+                if (s != s) atomicCAS(&err, 0, (int)STEP_ENAN);
+                key = ((u64)order_key(s) << 32) | (u32)tid;
+            }
+        }
+        keys[tid] = key;
+        lens[tid] = L;
+        const u64 live_mask = __ballot(key != ~0ull);
+        if ((tid & 63) == 0 && live_mask) atomicAdd(&live_count, __popcll(live_mask));
+    }
+    __syncthreads();
+    if (err == 0 && a.k > live_count) {
+        __syncthreads();
+        if (tid == 0) err = STEP_EKLIVE;
+    }
+    __syncthreads();
+    if (err != 0) {
+        if (tid == 0) {
+            report(a.status, err);
+            *a.n_freed = 0;
+        }
+        return;
+    }
+    // bitonic sort, ascending: one key per thread
+    {
+        u64 key = keys[tid];
+        for (int size = 2; size <= a.npad; size <<= 1) {
+            const bool asc = (tid & size) == 0;
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                u64 other;
+                if (stride >= 64) {
+                    __syncthreads();
+                    keys[tid] = key;
+                    __syncthreads();
+                    other = keys[tid ^ stride];
+                } else {
+                    const u32 lo = __shfl_xor((u32)key, stride), hi = __shfl_xor((u32)(key >> 32), stride);
+                    other = ((u64)hi << 32) | lo;
+                }
+                const bool take_min = ((tid & stride) == 0) == asc;
+                key = take_min ? (key < other ? key : other) : (key > other ? key : other);
+            }
+        }
+        __syncthreads();
+        keys[tid] = key;
+        __syncthreads();
+    }
+    if (tid < a.k) a.pruned[tid] = (int32_t)(u32)keys[tid];
+    // release: one (pruned trace, block-table entry) per thread and trip
+    const int entries = a.k * a.MAXB;
+    for (int e = tid; e < entries; e += kSelThreads) {
+        const int r = e / a.MAXB, j = e - r * a.MAXB;
+        const int t = (int)(u32)keys[r];
+        const int nb = (lens[t] + a.P - 1) / a.P;
+        int32_t *entry = a.block_tables + (size_t)t * a.MAXB + j;
+        if (j < nb) {
+            const int p = *entry;
+            if ((u32)p >= (u32)a.NP) {
+                report(a.status, STEP_EPAGE);
+            } else {
+                const int old = atomicSub(&a.refcounts[p], 1);
+                if (old <= 0) {
+                    atomicAdd(&a.refcounts[p], 1);
+                    report(a.status, STEP_EREFCOUNT);
+                } else if (old == 1) {
+                    atomicOr(&bitmap[p >> 5], 1u << (p & 31));
+                }
+            }
+        }
+        *entry = -1;
+    }
+    __syncthreads();
+    // compact the bitmap in ascending page order
+    const int per = (a.words + kSelThreads - 1) / kSelThreads;
+    const int w0 = min(tid * per, a.words), w1 = min(w0 + per, a.words);
+    int cnt = 0;
+    for (int wv = w0; wv < w1; ++wv) cnt += __popc(bitmap[wv]);
+    int total;
+    int pos = block_excl_scan(cnt, scratch, &total);
+    if (cnt > 0)
+        for (int wv = w0; wv < w1; ++wv) {
+            u32 bits = bitmap[wv];
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                a.freed_pages[pos++] = wv * 32 + b;
+            }
+        }
+    if (tid == 0) *a.n_freed = total;
+    if (tid < a.k) a.seq_lens[(int)(u32)keys[tid]] = 0;
 }
 
 }  // namespace
@@ -193,6 +363,11 @@ extern "C" int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const 
     a.words = (int)(((size_t)NP + 31) / 32);
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    static const bool force_multi = getenv("STEP_PRUNE_MULTI") != nullptr;  // testing aid: always three kernels
+    if (!force_multi && N <= kFusedN && a.words <= kFusedWords && (long long)k * MAXB <= kFusedEntries) {
+        hipLaunchKernelGGL(prune_fused, dim3(1), dim3(kSelThreads), 0, s, a);
+        return launch_status();
+    }
     hipLaunchKernelGGL(prune_select, dim3(1), dim3(kSelThreads), 0, s, a);
     if (k > 0 && MAXB > 0)
         hipLaunchKernelGGL(prune_release, dim3((MAXB + 255) / 256, k), dim3(256), 0, s, a);

@@ -4,8 +4,8 @@
 // Algorithm 1).
 //
 // score_hidden: the dense projection W1 X^T on the matrix cores (v_mfma_f32_16x16x32_bf16).  One
-//   workgroup owns 16 rows of W1 (one MFMA tile of hidden units) and up to 32 boundaries; its four
-//   waves split the contraction over d, 128 values per iteration, and are summed through LDS.  The
+//   workgroup owns 16 rows of W1 (one MFMA tile of hidden units) and up to 32 boundaries; its
+//   sixteen waves split the contraction over d, 128 values per iteration, and are summed through LDS.  The
 //   gather hidden[boundary_idx[b]] is fused into the B-operand loads.  Bias, activation and the
 //   product with the 16 matching entries of W2 follow in registers; the workgroup writes one
 //   partial logit per boundary.
@@ -17,7 +17,7 @@
 namespace step {
 namespace {
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 16;  // the contraction over d is split over the waves of a workgroup
 constexpr int kBT = 2;  // boundary tiles (of 16) per workgroup
 
 struct ScoreArgs {

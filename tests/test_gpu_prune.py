@@ -131,3 +131,41 @@ def test_host_reported_errors():
         binding.prune_free(scores, 1, dev(lay.refcounts), dev(lay.block_tables), dev(lay.seq_lens),
                            workspace=torch.zeros(256, dtype=torch.uint8, device=DEV))
     assert e.value.code == 2
+
+
+def test_fused_and_three_kernel_paths_agree():
+    """Small problems take the single-launch path, large ones three launches; both must give the
+    oracle's result.  The three-launch path is forced in a child process through its switch."""
+    import os, subprocess, sys, json
+    code = (
+        "import numpy as np, torch, json, sys\n"
+        "sys.path.insert(0, %r)\n"
+        "from paper_2601_09093_amd import binding, workloads as wl\n"
+        "lens = wl.rng_for(55, 0).integers(40, 600, 48)\n"
+        "lay = wl.build_layout(lens, 32, 16, wl.rng_for(55, 1), slack=1.2)\n"
+        "scores = wl.rng_for(55, 2).uniform(0, 1, 48).astype(np.float32)\n"
+        "d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to('cuda:0')\n"
+        "rc, bt, sl = d(lay.refcounts), d(lay.block_tables), d(lay.seq_lens)\n"
+        "st = torch.zeros(1, dtype=torch.int32, device='cuda:0')\n"
+        "pr, fr, nf = binding.prune_free(d(scores), 5, rc, bt, sl, status=st)\n"
+        "torch.cuda.synchronize()\n"
+        "print(json.dumps(dict(status=int(st.item()), pruned=pr.cpu().tolist()[:5], freed=fr.cpu().tolist()[:int(nf.item())],"
+        " rc=rc.cpu().tolist(), sl=sl.cpu().tolist(), bt=int(bt.cpu().numpy().astype(np.int64).sum()))))\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    outs = []
+    for multi in (False, True):
+        env = dict(os.environ)
+        env.pop("STEP_PRUNE_MULTI", None)
+        if multi:
+            env["STEP_PRUNE_MULTI"] = "1"
+        res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+        assert res.returncode == 0, res.stderr[-2000:]
+        outs.append(json.loads(res.stdout.strip().splitlines()[-1]))
+    assert outs[0] == outs[1] and outs[0]["status"] == 0
+    lens = wl.rng_for(55, 0).integers(40, 600, 48)
+    lay = wl.build_layout(lens, 32, P, wl.rng_for(55, 1), slack=1.2)
+    scores = wl.rng_for(55, 2).uniform(0, 1, 48).astype(np.float32)
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    pruned, freed = oracle.prune_free(scores, 5, rc, bt, sl, P)
+    assert outs[0]["pruned"] == pruned.tolist() and outs[0]["freed"] == freed.tolist()
+    assert outs[0]["rc"] == rc.tolist() and outs[0]["sl"] == sl.tolist()
