@@ -149,6 +149,49 @@ def test_host_reported_errors():
     torch.cuda.synchronize()
 
 
+def _shared_layout(seed, lens, shared_pages, P=16, extra_pool=7):
+    """Traces whose first `shared_pages` block-table entries are identical (caller keeps lens >= them)."""
+    lens = np.asarray(lens)
+    lay = wl.build_layout(lens, shared_pages * P, P, wl.rng_for(seed, 0), slack=1.1)
+    return lay
+
+
+@pytest.mark.parametrize("case", ["many_short", "more_traces_than_waves", "single_trace", "all_shared",
+                                  "long_prefix", "prefix_ends_ragged", "two_traces"])
+def test_planner_corner_cases(case):
+    """Shapes that push the work planner: shared-prefix detection, sub-chunking, runs that span many
+    traces, more live traces than waves per KV head, traces that lie entirely inside the prefix."""
+    r = wl.rng_for(900, 0)
+    D, Hq, Hkv = 128, 8, 2
+    if case == "many_short":
+        lens = r.integers(1, 40, 300); lens[::7] = 0
+        lay = wl.build_layout(lens, 0, P, wl.rng_for(901, 0), slack=1.2)
+    elif case == "more_traces_than_waves":
+        lens = 32 + r.integers(1, 200, 1500)                 # 1500 live traces, 2 shared pages
+        lay = wl.build_layout(lens, 32, P, wl.rng_for(902, 0), slack=1.0)
+        Hq, Hkv = 32, 8
+    elif case == "single_trace":
+        lay = wl.build_layout(np.array([0, 0, 5000, 0]), 0, P, wl.rng_for(903, 0))
+    elif case == "all_shared":
+        lay = wl.build_layout(np.array([160, 160, 160]), 160, P, wl.rng_for(904, 0))   # nothing private
+    elif case == "long_prefix":
+        lens = 300 * 16 + r.integers(1, 900, 5)              # 300 shared pages, above the 256-page search cap
+        lay = wl.build_layout(lens, 300 * 16, P, wl.rng_for(905, 0))
+    elif case == "prefix_ends_ragged":
+        lens = np.array([64 + 9, 64 + 9, 64 + 700])
+        lay = wl.build_layout(lens, 64, P, wl.rng_for(906, 0))
+        lay.block_tables[1, 4] = lay.block_tables[0, 4]      # traces 0 and 1 also share their ragged last page
+    else:
+        lens = np.array([4000, 17])
+        lay = wl.build_layout(lens, 16, P, wl.rng_for(907, 0))
+    N = lay.seq_lens.size
+    q = wl.normal_bf16(wl.rng_for(908, 1), (N, Hq, D))
+    k = wl.normal_bf16(wl.rng_for(908, 2), (lay.NP, Hkv, P, D))
+    v = wl.normal_bf16(wl.rng_for(908, 3), (lay.NP, Hkv, P, D))
+    wl.poison_unused(k, v, lay, P)
+    check(q, k, v, lay.block_tables, lay.seq_lens)
+
+
 def test_full_config2():
     w = wl.make_workload(2)
     check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
