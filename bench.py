@@ -31,7 +31,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 5], help="BASELINE.json config (1-based)")
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5], help="BASELINE.json config (1-based)")
+    ap.add_argument("--layers", type=int, default=None, help="layers per step (default: the config's; config 4: 36)")
     ap.add_argument("--prune-k", type=int, default=None, help="traces pruned per step (default 1; config 5: 64)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -96,18 +97,33 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
     # ---- resident inputs -------------------------------------------------------------------
+    layers = args.layers if args.layers is not None else w.layers
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.seed)
     kv_shape = (lay.NP, s.Hkv, s.P, s.D)
-    k_pages = torch.empty(kv_shape, dtype=torch.bfloat16, device=dev)
-    v_pages = torch.empty(kv_shape, dtype=torch.bfloat16, device=dev)
-    step_pages = max(1, (1 << 28) // (s.Hkv * s.P * s.D))           # draw in <=1 GiB fp32 pieces
-    for arr in (k_pages, v_pages):
-        for p0 in range(0, lay.NP, step_pages):
-            p1 = min(lay.NP, p0 + step_pages)
-            arr[p0:p1] = torch.randn((p1 - p0,) + kv_shape[1:], generator=gen, device=dev, dtype=torch.float32)
+    need = 2 * layers * lay.NP * s.Hkv * s.P * s.D * 2
+    free_b, _ = torch.cuda.mem_get_info()
+    if need > free_b - (8 << 30):
+        print("bench.py: config %d with %d layers needs %.1f GB of KV, %.1f GB free" % (
+            args.config, layers, need / 1e9, free_b / 1e9), file=sys.stderr)
+        sys.exit(4)
+    k_layers, v_layers = [], []
+    step_pages = max(1, (1 << 29) // (s.Hkv * s.P * s.D))           # draw in 1 GiB pieces
+    for _ in range(layers):
+        pair = []
+        for _kv in range(2):
+            arr = torch.empty(kv_shape, dtype=torch.bfloat16, device=dev)
+            for p0 in range(0, lay.NP, step_pages):
+                p1 = min(lay.NP, p0 + step_pages)
+                arr[p0:p1].normal_(generator=gen)
+            pair.append(arr)
+        k_layers.append(pair[0])
+        v_layers.append(pair[1])
+    k_pages, v_pages = k_layers[0], v_layers[0]
     q = bits(w.q)
     out = torch.empty_like(q)
+    q_layers = [q] + [torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+                      for _ in range(layers - 1)]
     hidden, W1, W2 = bits(sc.hidden), bits(sc.W1), bits(sc.W2)
     b1 = t(sc.b1)
     b2 = torch.tensor([sc.b2], dtype=torch.float32, device=dev)
@@ -138,7 +154,13 @@ def main():
     ws_prune = binding.new_workspace(binding.prune_workspace_bytes(s.N, lay.MAXB, lay.NP), dev)
 
     def step(i):
-        binding.paged_decode_attn(q, k_pages, v_pages, bt_s[i], sl_s[i], out=out, workspace=ws_attn, status=status)
+        if layers == 1:
+            binding.paged_decode_attn(q, k_pages, v_pages, bt_s[i], sl_s[i], out=out, workspace=ws_attn, status=status)
+        else:  # one plan per step, shared by every layer's attention
+            binding.attn_plan(q, k_pages, bt_s[i], sl_s[i], ws_attn, status=status)
+            for l in range(layers):
+                binding.paged_decode_attn_planned(q_layers[l], k_layers[l], v_layers[l], bt_s[i], sl_s[i], out,
+                                                  ws_attn, status=status)
         binding.step_score(hidden, bidx, W1, b1, W2, b2, act=sc.act, logits=logits, probs=probs, trace_of=trace_of,
                            score_sum=sum_s[i], score_cnt=cnt_s[i], scores=scores, workspace=ws_score, status=status)
         binding.prune_free(scores, prune_k, rc_s[i], bt_s[i], sl_s[i], pruned=pruned, freed_pages=freed,
@@ -155,11 +177,11 @@ def main():
     t1 = time.perf_counter()
     # the same K steps again with HIP events around the stage-1 attention kernel of every step (the
     # event records cost a few microseconds each, so they stay out of the step time above)
-    binding.attn_profile_begin(K)
+    binding.attn_profile_begin(K * layers)
     for i in range(W + K, W + 2 * K):
         step(i)
     torch.cuda.synchronize()
-    stage1_ms = binding.attn_profile_end(K)
+    stage1_ms = binding.attn_profile_end(K * layers)
     assert int(status.item()) == 0, binding.ERROR_NAMES.get(int(status.item()))
     assert int(n_freed.item()) > 0 or prune_k == 0
 
@@ -187,12 +209,12 @@ def main():
     }
 
     result = {
-        "metric": "paged decode-attn HBM GB/s (% of peak) + trace-tokens/s per step at N=64",
+        "metric": "paged decode-attn HBM GB/s (%% of peak) + trace-tokens/s per step at N=%d" % s.N,
         "value": round(value, 1), "unit": "trace-tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": workload, "N": s.N, "Hq": s.Hq, "Hkv": s.Hkv, "D": s.D, "page_tokens": s.P,
-                   "layers": 1, "prompt_tokens": lay.prompt_len, "context_tokens_total": lay.requested_tokens,
+                   "layers": layers, "prompt_tokens": lay.prompt_len, "context_tokens_total": lay.requested_tokens,
                    "unique_kv_tokens": lay.unique_tokens, "pool_pages": lay.NP, "scorer": "%d->%d->1 %s, B=%d" % (
                        sc.hidden.shape[1], sc.W1.shape[0], "ReLU" if sc.act == 0 else "GELU", B),
                    "prune_k": prune_k, "attn_waves_per_kv_head": binding.attn_waves_per_head(adims),
@@ -202,11 +224,11 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k)
+        result["cpu_baseline"] = cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k, layers)
     print(json.dumps(result))
 
 
-def cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k):
+def cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k, layers=1):
     """The oracle, as it stands, on the host cores: the whole step on a bounded sample of traces."""
     import numpy as np
     import torch
@@ -247,13 +269,14 @@ def cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k):
     scores = oracle.running_mean(sc.trace_of, probs.astype(np.float32), ssum, cnt)
     oracle.prune_free(scores, prune_k, lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy(), P)
     t_rest = time.perf_counter() - t0
-    total = t_attn + t_rest
+    total = t_attn * layers + t_rest   # several layers: one layer's attention timed, the rest extrapolated
     return {
         "value": round(traces.size / total, 3), "unit": "trace-tokens/s", "cores": threads, "kind": "oracle",
         "sample": "oracle attention on %d of %d traces (every %d-th by length, %d context tokens), plus the full "
-                  "scorer (B=%d), running mean and prune_free(k=%d); %.2f s attention + %.3f s rest" % (
+                  "scorer (B=%d), running mean and prune_free(k=%d); %.2f s attention per layer (x%d layers%s) + %.3f s rest" % (
                       traces.size, s.N, max(1, len(order) // max(traces.size, 1)), int(sl.sum()),
-                      sc.boundary_idx.size, prune_k, t_attn, t_rest),
+                      sc.boundary_idx.size, prune_k, t_attn, layers, ", extrapolated from layer 0" if layers > 1 else "",
+                      t_rest),
         "seconds": round(total, 3),
     }
 

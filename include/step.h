@@ -95,6 +95,22 @@ int paged_decode_attn(const step_attn_dims *dims, const uint16_t *q, const uint1
                       const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
                       uint16_t *out, void *workspace, size_t workspace_bytes, int32_t *status, void *stream);
 
+/*
+ * The same call in two halves, for a model with several layers: all layers of one decode step see
+ * the same block_tables and seq_lens, so the split of the work is planned once per step and every
+ * layer's attention reuses it.  step_attn_plan writes the plan into `workspace`;
+ * paged_decode_attn_planned is paged_decode_attn without the planning kernel and must be given the
+ * same dims, block_tables, seq_lens and workspace, unchanged since the plan was made (the layers run
+ * one after another on one stream and share the workspace).  Same arguments, layouts and errors as
+ * paged_decode_attn.
+ */
+int step_attn_plan(const step_attn_dims *dims, const int32_t *block_tables, const int32_t *seq_lens,
+                   void *workspace, size_t workspace_bytes, int32_t *status, void *stream);
+int paged_decode_attn_planned(const step_attn_dims *dims, const uint16_t *q, const uint16_t *k_pages,
+                              const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
+                              uint16_t *out, void *workspace, size_t workspace_bytes, int32_t *status,
+                              void *stream);
+
 /* ------------------------------------------------------------------------------------------ */
 /* Step scorer + running-mean trace score (Section 4.1 equation, Section 4.3 equation).        */
 /* ------------------------------------------------------------------------------------------ */

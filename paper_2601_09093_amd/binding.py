@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("STEP_LIBSTEP_PATH") or os.path.join(_HERE, "libstep.so")
+LIB_PATH = os.path.join(_HERE, "libstep.so")
 _lib = None
 
 STEP_OK = 0
@@ -57,6 +57,10 @@ def lib():
     L.step_attn_waves_per_head.argtypes = [ctypes.POINTER(AttnDims)]
     L.paged_decode_attn.restype = ctypes.c_int
     L.paged_decode_attn.argtypes = [ctypes.POINTER(AttnDims), vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+    L.step_attn_plan.restype = ctypes.c_int
+    L.step_attn_plan.argtypes = [ctypes.POINTER(AttnDims), vp, vp, vp, sz, vp, vp]
+    L.paged_decode_attn_planned.restype = ctypes.c_int
+    L.paged_decode_attn_planned.argtypes = [ctypes.POINTER(AttnDims), vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
     L.step_score_workspace_bytes.restype = sz
     L.step_score_workspace_bytes.argtypes = [ctypes.POINTER(ScoreDims)]
     L.step_score.restype = ctypes.c_int
@@ -134,6 +138,31 @@ def paged_decode_attn(q, k_pages, v_pages, block_tables, seq_lens, out=None, sca
         _dev(status, (torch.int32,), "status", True), _stream())
     if rc != STEP_OK:
         raise StepError(rc, "paged_decode_attn")
+    return out
+
+
+def attn_plan(q, k_pages, block_tables, seq_lens, workspace, scale=None, status=None):
+    """Plan one decode step's attention work into `workspace` (shared by all layers of the step)."""
+    dims = attn_dims(q, k_pages, block_tables, scale)
+    rc = lib().step_attn_plan(ctypes.byref(dims), _dev(block_tables, (torch.int32,), "block_tables"),
+                              _dev(seq_lens, (torch.int32,), "seq_lens"), _dev(workspace, (torch.uint8,), "workspace"),
+                              workspace.numel(), _dev(status, (torch.int32,), "status", True), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "step_attn_plan")
+    return dims
+
+
+def paged_decode_attn_planned(q, k_pages, v_pages, block_tables, seq_lens, out, workspace, scale=None, status=None):
+    """paged_decode_attn without the planning kernel; `workspace` holds the plan made by attn_plan."""
+    dims = attn_dims(q, k_pages, block_tables, scale)
+    rc = lib().paged_decode_attn_planned(
+        ctypes.byref(dims), _dev(q, _BF16_OK, "q"), _dev(k_pages, _BF16_OK, "k_pages"),
+        _dev(v_pages, _BF16_OK, "v_pages"), _dev(block_tables, (torch.int32,), "block_tables"),
+        _dev(seq_lens, (torch.int32,), "seq_lens"), _dev(out, _BF16_OK, "out"),
+        _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(),
+        _dev(status, (torch.int32,), "status", True), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "paged_decode_attn_planned")
     return out
 
 

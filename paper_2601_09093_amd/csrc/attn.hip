@@ -533,17 +533,6 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     float m_own, l_own, mx_pending;
 
     auto phaseA = [&](const uint4 (&k)[IPP], int slot, int ntok) {
-#ifdef STEP_EXP_NO_QK
-        {
-            u32 x = 0;
-#pragma unroll
-            for (int jj = 0; jj < IPP; ++jj) x ^= k[jj].x ^ k[jj].y ^ k[jj].z ^ k[jj].w;
-            l_own += __uint_as_float(x & 0x3fffffffu);
-            pbuf[slot][lane] = x;
-            (void)ntok;
-            return;
-        }
-#endif
         float val[NV];
 #pragma unroll
         for (int j = 0; j < IPP; ++j)
@@ -585,16 +574,6 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     };
 
     auto pv_pairs = [&](const uint4 (&v)[IPP], int slot) {
-#ifdef STEP_EXP_NO_PV
-        {
-            u32 x = 0;
-#pragma unroll
-            for (int jj = 0; jj < IPP; ++jj) x ^= v[jj].x ^ v[jj].y ^ v[jj].z ^ v[jj].w;
-            acc[0][0] += __uint_as_float(x & 0x3fffffffu);
-            (void)slot;
-            return;
-        }
-#endif
         const uint4 *pb = reinterpret_cast<const uint4 *>(&pbuf[slot][r * LPR]);
 #pragma unroll
         for (int pr = 0; pr < NPAIR; ++pr) {
@@ -918,46 +897,36 @@ struct Profile {
     int cap = 0, used = 0;
 } g_prof;
 
+enum : int { kDoPlan = 1, kDoAttend = 2 };
+
 template <int D, int G>
-int launch(const AttnArgs &a, hipStream_t s)
+int launch(const AttnArgs &a, hipStream_t s, int what)
 {
-    hipLaunchKernelGGL(attn_plan, dim3(1), dim3(kPlanThreads), 0, s, a);
-    const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
-    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], s);
-    if constexpr (G == 4)
-        hipLaunchKernelGGL((attn_partial_g4<D>), dim3((u32)(a.Wh * a.Hkv)), dim3(64), 0, s, a);
-    else
-        hipLaunchKernelGGL((attn_partial<D, G>), dim3((u32)(a.max_records * a.Hkv)), dim3(64), 0, s, a);
-    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used++ + 1], s);
-    hipLaunchKernelGGL((attn_merge<D, G>), dim3((u32)(a.N * a.Hq)), dim3(64), 0, s, a);
+    if (what & kDoPlan) hipLaunchKernelGGL(attn_plan, dim3(1), dim3(kPlanThreads), 0, s, a);
+    if (what & kDoAttend) {
+        const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
+        if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], s);
+        if constexpr (G == 4)
+            hipLaunchKernelGGL((attn_partial_g4<D>), dim3((u32)(a.Wh * a.Hkv)), dim3(64), 0, s, a);
+        else
+            hipLaunchKernelGGL((attn_partial<D, G>), dim3((u32)(a.max_records * a.Hkv)), dim3(64), 0, s, a);
+        if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used++ + 1], s);
+        hipLaunchKernelGGL((attn_merge<D, G>), dim3((u32)(a.N * a.Hq)), dim3(64), 0, s, a);
+    }
     return launch_status();
 }
 
-}  // namespace
-}  // namespace step
-
-using namespace step;
-
-extern "C" int32_t step_attn_waves_per_head(const step_attn_dims *d)
-{
-    return dims_ok(d) ? waves_per_head(d) : 0;
-}
-
-extern "C" size_t step_attn_workspace_bytes(const step_attn_dims *d)
-{
-    if (!dims_ok(d)) return 0;
-    return layout_for(d).total;
-}
-
-extern "C" int paged_decode_attn(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages,
-                                 const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
-                                 uint16_t *out, void *workspace, size_t workspace_bytes, int32_t *status,
-                                 void *stream)
+int run(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages, const uint16_t *v_pages,
+        const int32_t *block_tables, const int32_t *seq_lens, uint16_t *out, void *workspace,
+        size_t workspace_bytes, int32_t *status, void *stream, int what)
 {
     if (!dims_ok(d)) return STEP_EINVAL;
     if (d->N == 0) return STEP_OK;
-    if (!q || !k_pages || !v_pages || !block_tables || !seq_lens || !out) return STEP_EINVAL;
-    if (!aligned(q, 16) || !aligned(k_pages, 16) || !aligned(v_pages, 16) || !aligned(out, 4)) return STEP_EINVAL;
+    if (!block_tables || !seq_lens) return STEP_EINVAL;
+    if (what & kDoAttend) {
+        if (!q || !k_pages || !v_pages || !out) return STEP_EINVAL;
+        if (!aligned(q, 16) || !aligned(k_pages, 16) || !aligned(v_pages, 16) || !aligned(out, 4)) return STEP_EINVAL;
+    }
     const Layout l = layout_for(d);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < l.total) return STEP_EWORKSPACE;
 
@@ -981,16 +950,57 @@ extern "C" int paged_decode_attn(const step_attn_dims *d, const uint16_t *q, con
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const int key = d->D * 16 + d->Hq / d->Hkv;
     switch (key) {
-        case 64 * 16 + 1: return launch<64, 1>(a, s);
-        case 64 * 16 + 2: return launch<64, 2>(a, s);
-        case 64 * 16 + 4: return launch<64, 4>(a, s);
-        case 64 * 16 + 8: return launch<64, 8>(a, s);
-        case 128 * 16 + 1: return launch<128, 1>(a, s);
-        case 128 * 16 + 2: return launch<128, 2>(a, s);
-        case 128 * 16 + 4: return launch<128, 4>(a, s);
-        case 128 * 16 + 8: return launch<128, 8>(a, s);
+        case 64 * 16 + 1: return launch<64, 1>(a, s, what);
+        case 64 * 16 + 2: return launch<64, 2>(a, s, what);
+        case 64 * 16 + 4: return launch<64, 4>(a, s, what);
+        case 64 * 16 + 8: return launch<64, 8>(a, s, what);
+        case 128 * 16 + 1: return launch<128, 1>(a, s, what);
+        case 128 * 16 + 2: return launch<128, 2>(a, s, what);
+        case 128 * 16 + 4: return launch<128, 4>(a, s, what);
+        case 128 * 16 + 8: return launch<128, 8>(a, s, what);
     }
     return STEP_EINVAL;
+}
+
+}  // namespace
+}  // namespace step
+
+using namespace step;
+
+extern "C" int32_t step_attn_waves_per_head(const step_attn_dims *d)
+{
+    return dims_ok(d) ? waves_per_head(d) : 0;
+}
+
+extern "C" size_t step_attn_workspace_bytes(const step_attn_dims *d)
+{
+    if (!dims_ok(d)) return 0;
+    return layout_for(d).total;
+}
+
+extern "C" int paged_decode_attn(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages,
+                                 const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
+                                 uint16_t *out, void *workspace, size_t workspace_bytes, int32_t *status,
+                                 void *stream)
+{
+    return run(d, q, k_pages, v_pages, block_tables, seq_lens, out, workspace, workspace_bytes, status, stream,
+               kDoPlan | kDoAttend);
+}
+
+extern "C" int step_attn_plan(const step_attn_dims *d, const int32_t *block_tables, const int32_t *seq_lens,
+                              void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
+{
+    return run(d, nullptr, nullptr, nullptr, block_tables, seq_lens, nullptr, workspace, workspace_bytes, status,
+               stream, kDoPlan);
+}
+
+extern "C" int paged_decode_attn_planned(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages,
+                                         const uint16_t *v_pages, const int32_t *block_tables,
+                                         const int32_t *seq_lens, uint16_t *out, void *workspace,
+                                         size_t workspace_bytes, int32_t *status, void *stream)
+{
+    return run(d, q, k_pages, v_pages, block_tables, seq_lens, out, workspace, workspace_bytes, status, stream,
+               kDoAttend);
 }
 
 extern "C" int step_attn_profile_begin(int cap)

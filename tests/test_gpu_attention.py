@@ -236,3 +236,81 @@ def test_full_size_sampled_rows(cfg):
     err = np.abs(sel - want)
     assert err.max() <= TOL
     assert np.all(err <= 2.0 ** -8 * np.abs(want) + 4e-3), float(err.max())
+
+
+def test_one_plan_shared_by_several_layers():
+    """Config 4's structure, scaled down: lognormal lengths, one plan per step, every layer's
+    attention (own K/V pool, own q, same block tables) reuses it."""
+    w = wl.make_workload(4, kv=False, N=12)
+    lay, s = w.layout, w.shape
+    layers = 3
+    ws = binding.new_workspace(binding.attn_workspace_bytes(
+        binding.AttnDims(s.N, s.Hq, s.Hkv, s.D, P, lay.MAXB, lay.NP, s.D ** -0.5)), DEV)
+    bt, sl = dev(lay.block_tables), dev(lay.seq_lens)
+    st = new_status()
+    qs = [wl.normal_bf16(wl.rng_for(40 + l, 1), (s.N, s.Hq, s.D)) for l in range(layers)]
+    ks = [wl.normal_bf16(wl.rng_for(40 + l, 2), (lay.NP, s.Hkv, P, s.D)) for l in range(layers)]
+    vs = [wl.normal_bf16(wl.rng_for(40 + l, 3), (lay.NP, s.Hkv, P, s.D)) for l in range(layers)]
+    tq, tk, tv = [dev_bits(x) for x in qs], [dev_bits(x) for x in ks], [dev_bits(x) for x in vs]
+    binding.attn_plan(tq[0], tk[0], bt, sl, ws, status=st)
+    outs = []
+    for l in range(layers):
+        out = torch.empty_like(tq[l])
+        binding.paged_decode_attn_planned(tq[l], tk[l], tv[l], bt, sl, out, ws, status=st)
+        outs.append(out)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    for l in range(layers):
+        want = oracle.paged_decode_attn(qs[l], ks[l], vs[l], lay.block_tables, lay.seq_lens)
+        got = host_f32_of_bf16(outs[l])
+        assert np.abs(got - want).max() <= TOL
+        # and bit-identical to the one-call form
+        one = binding.paged_decode_attn(tq[l], tk[l], tv[l], bt, sl, status=st)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(one), host_bits(outs[l]))
+
+
+def test_config4_full_sweep_sampled_layers():
+    """Config 4 at full size: 36 layers, N = 128 traces with lognormal lengths, ~210 GB of bf16 KV
+    drawn on the device, one plan for the step, 36 attention calls; parity on layers 0, 17 and 35
+    for sampled (trace, head) rows.  Skipped when the device does not have the memory free."""
+    w = wl.make_workload(4, kv=False)
+    lay, s = w.layout, w.shape
+    layers = w.layers
+    need = 2 * layers * lay.NP * s.Hkv * P * s.D * 2
+    free_b, _ = torch.cuda.mem_get_info()
+    if need > free_b - (12 << 30):
+        pytest.skip("needs %.0f GB of device memory, %.0f GB free" % (need / 1e9, free_b / 1e9))
+    g = torch.Generator(device=DEV); g.manual_seed(w.seed)
+    shape = (lay.NP, s.Hkv, P, s.D)
+    ks = [torch.empty(shape, dtype=torch.bfloat16, device=DEV).normal_(generator=g) for _ in range(layers)]
+    vs = [torch.empty(shape, dtype=torch.bfloat16, device=DEV).normal_(generator=g) for _ in range(layers)]
+    qs = [torch.empty((s.N, s.Hq, s.D), dtype=torch.bfloat16, device=DEV).normal_(generator=g) for _ in range(layers)]
+    bt, sl = dev(lay.block_tables), dev(lay.seq_lens)
+    st = new_status()
+    ws = binding.new_workspace(binding.attn_workspace_bytes(binding.attn_dims(qs[0], ks[0], bt)), DEV)
+    outs = [torch.empty_like(qs[0]) for _ in range(layers)]
+    binding.attn_plan(qs[0], ks[0], bt, sl, ws, status=st)
+    for l in range(layers):
+        binding.paged_decode_attn_planned(qs[l], ks[l], vs[l], bt, sl, outs[l], ws, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    order = np.argsort(lay.seq_lens)
+    traces = np.unique([order[0], order[-1], order[len(order) // 2]])
+    heads = np.arange(s.Hkv) * (s.Hq // s.Hkv) + (np.arange(s.Hkv) % (s.Hq // s.Hkv))
+    pages = np.unique(np.concatenate([lay.block_tables[t][: (lay.seq_lens[t] + P - 1) // P] for t in traces]))
+    remap = -np.ones(lay.NP, np.int64); remap[pages] = np.arange(pages.size)
+    idx = torch.from_numpy(pages).to(DEV)
+    btr = np.where(lay.block_tables[traces] >= 0, remap[np.maximum(lay.block_tables[traces], 0)], -1).astype(np.int32)
+    slr = lay.seq_lens[traces].copy()
+    rows = (np.repeat(np.arange(traces.size), heads.size).astype(np.int32), np.tile(heads, traces.size).astype(np.int32))
+    for l in (0, 17, 35):
+        got = host_f32_of_bf16(outs[l])
+        assert np.all(np.isfinite(got))
+        kh = host_bits(ks[l].index_select(0, idx)); vh = host_bits(vs[l].index_select(0, idx))
+        qh = np.ascontiguousarray(host_bits(qs[l])[traces])
+        want = oracle.paged_decode_attn(qh, kh, vh, btr, slr, rows=rows)
+        err = np.abs(got[traces][rows[0], rows[1]] - want)
+        assert err.max() <= TOL, (l, float(err.max()))
+    del ks, vs
+    torch.cuda.empty_cache()
