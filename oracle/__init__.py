@@ -145,3 +145,56 @@ def prune_free(scores, k, refcounts, block_tables, seq_lens, P=16):
     if rc:
         raise OracleError(rc)
     return pruned, freed[: nf.value].copy()
+
+
+def reserve_pages(scores, refcounts, block_tables, seq_lens, P=16):
+    """In place on refcounts, block_tables, seq_lens.  Returns (pruned i32 in pruning order,
+    new_pages [N] i32: page given to each trace or -1)."""
+    lib = _load()
+    _chk(scores, np.float32, "scores"); _chk(refcounts, np.int32, "refcounts")
+    _chk(block_tables, np.int32, "block_tables"); _chk(seq_lens, np.int32, "seq_lens")
+    N, MAXB = block_tables.shape
+    NP = refcounts.shape[0]
+    pruned = np.full(max(N, 1), -1, np.int32)
+    new_pages = np.full(max(N, 1), -1, np.int32)
+    n = ctypes.c_int32(0)
+    rc = lib.oracle_reserve_pages(
+        N, MAXB, NP, int(P), _p(scores, ctypes.c_float), _p(refcounts, ctypes.c_int32),
+        _p(block_tables, ctypes.c_int32), _p(seq_lens, ctypes.c_int32), _p(pruned, ctypes.c_int32),
+        ctypes.byref(n), _p(new_pages, ctypes.c_int32))
+    if rc:
+        raise OracleError(rc)
+    return pruned[: n.value].copy(), new_pages[:N].copy()
+
+
+def append_kv(k_new, v_new, k_pages, v_pages, block_tables, refcounts, seq_lens):
+    """Writes row L_i of every live trace into its page (in place on k_pages, v_pages) and adds 1 to
+    seq_lens.  k_new, v_new: [N][Hkv][D] u16."""
+    lib = _load()
+    _chk(k_new, np.uint16, "k_new"); _chk(v_new, np.uint16, "v_new")
+    _chk(k_pages, np.uint16, "k_pages"); _chk(v_pages, np.uint16, "v_pages")
+    _chk(block_tables, np.int32, "block_tables"); _chk(seq_lens, np.int32, "seq_lens")
+    if refcounts is not None:
+        _chk(refcounts, np.int32, "refcounts")
+    N, Hkv, D = k_new.shape
+    NP, Hkv2, P, D2 = k_pages.shape
+    assert (Hkv2, D2) == (Hkv, D) and v_new.shape == k_new.shape and v_pages.shape == k_pages.shape
+    MAXB = block_tables.shape[1]
+    u16, i32 = ctypes.c_uint16, ctypes.c_int32
+    rc = lib.oracle_append_kv(N, Hkv, D, P, MAXB, NP, _p(k_new, u16), _p(v_new, u16), _p(k_pages, u16),
+                              _p(v_pages, u16), _p(block_tables, i32), _p(refcounts, i32), _p(seq_lens, i32))
+    if rc:
+        raise OracleError(rc)
+
+
+def weighted_vote(answer, scores):
+    """answer [N] i32 (-1: no answer), scores [N] f32.  Returns (winner, weight)."""
+    lib = _load()
+    _chk(answer, np.int32, "answer"); _chk(scores, np.float32, "scores")
+    w = ctypes.c_int32(-1)
+    wt = ctypes.c_float(0.0)
+    rc = lib.oracle_weighted_vote(answer.shape[0], _p(answer, ctypes.c_int32), _p(scores, ctypes.c_float),
+                                  ctypes.byref(w), ctypes.byref(wt))
+    if rc:
+        raise OracleError(rc)
+    return int(w.value), float(wt.value)

@@ -18,6 +18,11 @@
  *                               ReleaseKVCache(t*), T <- T \ {t*}, applied k times
  *                               (Section 4.2: prune lowest average score, release
  *                               its KV cache).
+ *   oracle_reserve_pages      - Section 4.2's trigger: prune one trace at a time
+ *                               while the next decode step cannot be scheduled,
+ *                               then hand out the new pages.
+ *   oracle_append_kv          - the KV-cache write of NextToken(t).
+ *   oracle_weighted_vote      - Section 4.3 / WeightedVote of Algorithm 1.
  *
  * All floating-point work is float64 on the exact values of the bf16/fp32
  * inputs, except the running-mean state, which is fp32 by definition of the
@@ -284,6 +289,148 @@ done:
     free(taken);
     free(rc);
     return err;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Memory trigger + page allocation (Section 4.2; Algorithm 1's GPUMemoryFull) */
+/* ------------------------------------------------------------------------ */
+
+/* Before the next decode step: a live trace whose length is a multiple of P
+ * opens a new page with its next token.  "GPU memory is full and the KV cache
+ * for the next decoding step cannot be scheduled" (Section 4.2) is read as:
+ * fewer free pages (refcount 0) than traces that need one.  While that holds,
+ * prune the live trace with the lowest score (ties: lowest index) and release
+ * its pages, exactly as oracle_prune_free does for k = 1.  Then every trace
+ * that still needs a page, in ascending trace index, takes the smallest free
+ * page id: block_tables[i][L_i / P] = page, refcounts[page] = 1.
+ * pruned[] (capacity N) lists the pruned traces in order, new_pages[i] is the
+ * page given to trace i or -1.  On an error nothing is modified. */
+int oracle_reserve_pages(int N, int MAXB, int NP, int P, const float *scores,
+                         int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens,
+                         int32_t *pruned, int32_t *n_pruned, int32_t *new_pages)
+{
+    if (N < 0 || MAXB < 0 || NP < 0 || P <= 0) return ORACLE_EINVAL;
+    int32_t *rc = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NP > 0 ? NP : 1));
+    int32_t *sl = (int32_t *)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    if (!rc || !sl) { free(rc); free(sl); return ORACLE_EINVAL; }
+    memcpy(rc, refcounts, sizeof(int32_t) * (size_t)NP);
+    memcpy(sl, seq_lens, sizeof(int32_t) * (size_t)N);
+    int err = ORACLE_OK, np = 0;
+    for (int i = 0; i < N; ++i)
+        if (sl[i] < 0 || (int64_t)sl[i] > (int64_t)MAXB * P) { err = ORACLE_ELEN; goto done; }
+    for (;;) {
+        int needed = 0, nfree = 0;
+        for (int i = 0; i < N; ++i)
+            if (sl[i] > 0 && sl[i] % P == 0) {
+                if (sl[i] / P >= MAXB) { err = ORACLE_ELEN; goto done; } /* row has no entry left */
+                ++needed;
+            }
+        for (int p = 0; p < NP; ++p)
+            if (rc[p] == 0) ++nfree;
+        if (nfree >= needed) break;
+        int best = -1;
+        for (int i = 0; i < N; ++i) {
+            if (sl[i] <= 0) continue;
+            if (isnan(scores[i])) { err = ORACLE_ENAN; goto done; }
+            if (best < 0 || scores[i] < scores[best]) best = i;
+        }
+        /* needed > 0 implies a live trace exists */
+        const int nb = (sl[best] + P - 1) / P;
+        for (int j = 0; j < nb; ++j) {
+            const int32_t p = block_tables[(int64_t)best * MAXB + j];
+            if (p < 0 || p >= NP) { err = ORACLE_EPAGE; goto done; }
+            if (rc[p] <= 0) { err = ORACLE_EREFCOUNT; goto done; }
+            rc[p] -= 1;
+        }
+        sl[best] = 0;
+        pruned[np++] = best;
+    }
+    /* commit: pruned rows, then allocation */
+    for (int r = 0; r < np; ++r) {
+        const int t = pruned[r];
+        for (int j = 0; j < MAXB; ++j) block_tables[(int64_t)t * MAXB + j] = -1;
+    }
+    {
+        int next = 0;
+        for (int i = 0; i < N; ++i) {
+            new_pages[i] = -1;
+            if (sl[i] > 0 && sl[i] % P == 0) {
+                while (rc[next] != 0) ++next; /* exists: nfree >= needed */
+                rc[next] = 1;
+                block_tables[(int64_t)i * MAXB + sl[i] / P] = next;
+                new_pages[i] = next;
+            }
+        }
+    }
+    memcpy(refcounts, rc, sizeof(int32_t) * (size_t)NP);
+    memcpy(seq_lens, sl, sizeof(int32_t) * (size_t)N);
+    *n_pruned = np;
+done:
+    free(rc);
+    free(sl);
+    return err;
+}
+
+/* Append the newest token's K and V rows (k_new, v_new: [N][Hkv][D] bf16) to
+ * every live trace: row L_i of trace i lives in page block_tables[i][L_i / P],
+ * slot L_i % P; then L_i += 1.  This is the KV-cache write of NextToken(t) in
+ * Algorithm 1 (the paper leaves it to the serving engine).  A page written to
+ * must be private (refcount 1).  On an error nothing is modified. */
+int oracle_append_kv(int N, int Hkv, int D, int P, int MAXB, int NP,
+                     const uint16_t *k_new, const uint16_t *v_new, uint16_t *k_pages, uint16_t *v_pages,
+                     const int32_t *block_tables, const int32_t *refcounts, int32_t *seq_lens)
+{
+    if (N < 0 || Hkv <= 0 || D <= 0 || P <= 0 || MAXB < 0 || NP < 0) return ORACLE_EINVAL;
+    for (int i = 0; i < N; ++i) {
+        const int64_t L = seq_lens[i];
+        if (L < 0 || L > (int64_t)MAXB * P) return ORACLE_ELEN;
+        if (L == 0) continue;
+        if (L == (int64_t)MAXB * P) return ORACLE_ELEN;
+        const int32_t p = block_tables[(int64_t)i * MAXB + L / P];
+        if (p < 0 || p >= NP) return ORACLE_EPAGE;
+        if (refcounts && refcounts[p] != 1) return ORACLE_EREFCOUNT;
+    }
+    for (int i = 0; i < N; ++i) {
+        const int64_t L = seq_lens[i];
+        if (L == 0) continue;
+        const int32_t p = block_tables[(int64_t)i * MAXB + L / P];
+        const int s = (int)(L % P);
+        for (int g = 0; g < Hkv; ++g) {
+            const int64_t dst = (((int64_t)p * Hkv + g) * P + s) * D;
+            const int64_t src = ((int64_t)i * Hkv + g) * D;
+            memcpy(k_pages + dst, k_new + src, sizeof(uint16_t) * (size_t)D);
+            memcpy(v_pages + dst, v_new + src, sizeof(uint16_t) * (size_t)D);
+        }
+        seq_lens[i] = (int32_t)(L + 1);
+    }
+    return ORACLE_OK;
+}
+
+/* Weighted majority vote over the final answers (Section 4.3; WeightedVote in
+ * Algorithm 1): answer[i] >= 0 is the answer id of a finished trace, -1 means
+ * the trace has none (pruned or unfinished).  The weight of an answer is the
+ * fp32 sum, in trace index order, of the scores of the traces that gave it;
+ * the winner has the largest weight (ties: smallest answer id).  Returns -1 in
+ * *winner when nobody answered. */
+int oracle_weighted_vote(int N, const int32_t *answer, const float *scores, int32_t *winner, float *weight)
+{
+    if (N < 0) return ORACLE_EINVAL;
+    int32_t best = -1;
+    float best_w = 0.0f;
+    for (int i = 0; i < N; ++i) {
+        if (answer[i] < 0) continue;
+        if (isnan(scores[i])) return ORACLE_ENAN;
+        float w = 0.0f;
+        for (int j = 0; j < N; ++j)
+            if (answer[j] == answer[i]) w = w + scores[j];
+        if (best < 0 || w > best_w || (w == best_w && answer[i] < best)) {
+            best = answer[i];
+            best_w = w;
+        }
+    }
+    *winner = best;
+    *weight = best_w;
+    return ORACLE_OK;
 }
 
 int oracle_num_threads(void)

@@ -1,0 +1,194 @@
+"""Pins of the oracle's memory trigger / page allocator (Section 4.2; Algorithm 1's GPUMemoryFull
+branch), KV append (the cache write of NextToken) and weighted vote (Section 4.3)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2601_09093_amd import workloads as wl
+from tests.helpers import dense_attention, gather_dense
+
+P = 16
+
+
+def _layout(seed, lens, prompt=0, slack=1.0, maxb=None):
+    return wl.build_layout(np.asarray(lens), prompt, P, wl.rng_for(seed, 1), slack=slack, maxb=maxb)
+
+
+def _consistent(rc, bt):
+    want = np.zeros_like(rc)
+    np.add.at(want, bt[bt >= 0], 1)
+    return np.array_equal(rc, want)
+
+
+def test_no_pressure_hands_out_smallest_free_ids_in_trace_order():
+    lay = _layout(1, [32, 40, 48, 16, 0], maxb=8, slack=1.0)
+    # grow the pool by 5 free pages with known ids
+    rc = np.concatenate([lay.refcounts, np.zeros(5, np.int32)])
+    bt, sl = lay.block_tables.copy(), lay.seq_lens.copy()
+    free_ids = np.nonzero(rc == 0)[0]
+    scores = np.array([0.5, 0.1, 0.9, 0.3, 0.0], np.float32)
+    pruned, new = oracle.reserve_pages(scores, rc, bt, sl, P)
+    assert pruned.size == 0
+    # traces 0 (L=32), 2 (L=48), 3 (L=16) sit on a page boundary; 1 (L=40) and the dead trace do not
+    assert new.tolist() == [free_ids[0], -1, free_ids[1], free_ids[2], -1]
+    assert bt[0, 2] == free_ids[0] and bt[2, 3] == free_ids[1] and bt[3, 1] == free_ids[2]
+    assert np.array_equal(sl, lay.seq_lens) and _consistent(rc, bt)
+
+
+def test_hand_example_full_pool_prunes_lowest_until_it_fits():
+    # 4 traces of 2 pages each in a pool of exactly 8 pages, all on a page boundary: 4 pages needed,
+    # 0 free.  Pruning the lowest (trace 2) frees 2 and lowers the need to 3; pruning the next
+    # lowest (trace 0) frees 2 more and lowers the need to 2: 4 free >= 2 needed.
+    lay = _layout(2, [32, 32, 32, 32], maxb=4)
+    assert lay.NP == 8
+    scores = np.array([0.2, 0.7, 0.1, 0.9], np.float32)
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    pruned, new = oracle.reserve_pages(scores, rc, bt, sl, P)
+    assert pruned.tolist() == [2, 0]
+    freed = sorted(lay.block_tables[2, :2].tolist() + lay.block_tables[0, :2].tolist())
+    assert new.tolist() == [-1, freed[0], -1, freed[1]]
+    assert sl.tolist() == [0, 32, 0, 32] and np.all(bt[0] == -1) and np.all(bt[2] == -1)
+    assert _consistent(rc, bt) and rc.sum() == 6
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_equals_smallest_k_prune_free_then_allocate(seed):
+    """reserve == prune_free(k) for the smallest k that makes the step schedulable, then allocation.
+    prune_free is pinned on its own; this pins the trigger's loop and the hand-out against it."""
+    r = wl.rng_for(100 + seed, 0)
+    N = 10
+    lens = 32 + 16 * r.integers(0, 5, N) + np.where(r.random(N) < 0.5, 0, r.integers(1, 16, N))
+    lay = wl.build_layout(lens, 32, P, wl.rng_for(100 + seed, 1), slack=1.0, maxb=12)
+    extra = int(r.integers(0, 3))
+    rc0 = np.concatenate([lay.refcounts, np.zeros(extra, np.int32)])
+    scores = r.uniform(0, 1, N).astype(np.float32)
+    scores[3] = scores[7]
+    rc, bt, sl = rc0.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    pruned, new = oracle.reserve_pages(scores, rc, bt, sl, P)
+    for k in range(N + 1):
+        rc2, bt2, sl2 = rc0.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+        p2, _ = oracle.prune_free(scores, k, rc2, bt2, sl2, P)
+        need = [i for i in range(N) if sl2[i] > 0 and sl2[i] % P == 0]
+        if (rc2 == 0).sum() >= len(need):
+            break
+    assert pruned.tolist() == p2.tolist()
+    free_ids = np.nonzero(rc2 == 0)[0]
+    for j, i in enumerate(need):
+        bt2[i, sl2[i] // P] = free_ids[j]
+        rc2[free_ids[j]] = 1
+    assert np.array_equal(rc, rc2) and np.array_equal(bt, bt2) and np.array_equal(sl, sl2)
+    assert [i for i in range(N) if new[i] >= 0] == need and _consistent(rc, bt)
+
+
+def test_shared_prompt_pages_survive_while_any_trace_lives():
+    lay = _layout(3, [64, 64, 64], prompt=32, maxb=6)
+    scores = np.array([0.3, 0.2, 0.1], np.float32)
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    pruned, new = oracle.reserve_pages(scores, rc, bt, sl, P)
+    # pool: 2 shared + 3*2 private = 8 pages, all used; 3 needed.  Prune trace 2 (frees 2, need 2).
+    assert pruned.tolist() == [2]
+    assert np.all(rc[lay.block_tables[0, :2]] == 2)
+    assert sorted(new[new >= 0].tolist()) == sorted(lay.block_tables[2, 2:4].tolist())
+
+
+def test_errors_leave_state_untouched():
+    lay = _layout(4, [32, 32], maxb=2)                      # rows are full: no entry for a new page
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.reserve_pages(np.zeros(2, np.float32), rc, bt, sl, P)
+    assert e.value.name == "ELEN" and np.array_equal(bt, lay.block_tables)
+    lay = _layout(5, [32, 32], maxb=4)
+    sc = np.array([np.nan, 0.5], np.float32)
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    with pytest.raises(oracle.OracleError) as e:            # pruning is needed and a live score is NaN
+        oracle.reserve_pages(sc, rc, bt, sl, P)
+    assert e.value.name == "ENAN" and np.array_equal(rc, lay.refcounts)
+    rc = np.concatenate([lay.refcounts, np.zeros(2, np.int32)])
+    pruned, new = oracle.reserve_pages(sc, rc, bt, sl, P)    # no pruning needed: NaN is never looked at
+    assert pruned.size == 0 and (new >= 0).all()
+
+
+def test_append_writes_exactly_one_row_per_live_trace():
+    lay = _layout(6, [17, 32, 0, 5], maxb=4, slack=1.5)
+    Hkv, D = 2, 8
+    k = wl.normal_bf16(wl.rng_for(6, 2), (lay.NP + 1, Hkv, P, D)); v = wl.normal_bf16(wl.rng_for(6, 3), k.shape)
+    rc = np.concatenate([lay.refcounts, [0]]).astype(np.int32)
+    bt, sl = lay.block_tables.copy(), lay.seq_lens.copy()
+    bt[1, 2] = lay.NP; rc[lay.NP] = 1                        # trace 1 (L = 32) got a fresh page
+    kn = wl.normal_bf16(wl.rng_for(6, 4), (4, Hkv, D)); vn = wl.normal_bf16(wl.rng_for(6, 5), (4, Hkv, D))
+    k0, v0 = k.copy(), v.copy()
+    oracle.append_kv(kn, vn, k, v, bt, rc, sl)
+    assert sl.tolist() == [18, 33, 0, 6]
+    changed = np.zeros(k.shape[:3], bool)
+    for i, L in ((0, 17), (1, 32), (3, 5)):
+        page, slot = bt[i, L // P], L % P
+        assert np.array_equal(k[page, :, slot], kn[i]) and np.array_equal(v[page, :, slot], vn[i])
+        changed[page, :, slot] = True
+    assert np.array_equal(k[~changed], k0[~changed]) and np.array_equal(v[~changed], v0[~changed])
+
+
+def test_append_then_attention_sees_the_new_token():
+    lay = _layout(7, [20, 33], maxb=4, slack=1.0)
+    Hkv, D = 1, 8
+    k = wl.normal_bf16(wl.rng_for(7, 2), (lay.NP, Hkv, P, D)); v = wl.normal_bf16(wl.rng_for(7, 3), k.shape)
+    q = wl.normal_bf16(wl.rng_for(7, 4), (2, 2, D))
+    kn = wl.normal_bf16(wl.rng_for(7, 5), (2, Hkv, D)); vn = wl.normal_bf16(wl.rng_for(7, 6), (2, Hkv, D))
+    sl = lay.seq_lens.copy()
+    oracle.append_kv(kn, vn, k, v, lay.block_tables, lay.refcounts, sl)
+    got = oracle.paged_decode_attn(q, k, v, lay.block_tables, sl)
+    # dense check: the last key/value row of each trace is the appended one
+    for i in range(2):
+        K = gather_dense(k, lay.block_tables[i], int(sl[i]), 0, P)
+        assert np.array_equal(K[-1], wl.bf16_bits_to_f32(kn[i, 0]).astype(np.float64))
+    np.testing.assert_allclose(got, dense_attention(q, k, v, lay.block_tables, sl, 8 ** -0.5), rtol=1e-12)
+
+
+def test_append_errors():
+    lay = _layout(8, [16, 20], maxb=2, slack=1.0)
+    Hkv, D = 1, 8
+    k = np.zeros((lay.NP, Hkv, P, D), np.uint16); v = k.copy()
+    kn = np.ones((2, Hkv, D), np.uint16)
+    sl = lay.seq_lens.copy()
+    with pytest.raises(oracle.OracleError) as e:            # trace 0 needs page index 1: entry is -1
+        oracle.append_kv(kn, kn, k, v, lay.block_tables, lay.refcounts, sl)
+    assert e.value.name == "EPAGE" and np.array_equal(sl, lay.seq_lens) and not k.any()
+    lay2 = _layout(9, [20, 20], prompt=16, maxb=2)
+    bt = lay2.block_tables.copy(); bt[:, 1] = bt[0, 1]      # both traces would write into one page
+    rc = lay2.refcounts.copy(); rc[bt[0, 1]] = 2
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.append_kv(kn, kn, np.zeros((lay2.NP, 1, P, D), np.uint16), np.zeros((lay2.NP, 1, P, D), np.uint16),
+                         bt, rc, lay2.seq_lens.copy())
+    assert e.value.name == "EREFCOUNT"
+    sl = np.array([32, 20], np.int32)                        # row full
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.append_kv(kn, kn, k, v, lay.block_tables, None, sl)
+    assert e.value.name == "ELEN"
+
+
+def test_weighted_vote_hand_cases():
+    a = np.array([7, 3, 7, -1, 3, 9], np.int32)
+    s = np.array([0.25, 0.5, 0.5, 9.0, 0.125, 0.7], np.float32)
+    assert oracle.weighted_vote(a, s) == (7, 0.75)           # 7: 0.75, 3: 0.625, 9: 0.7; the -1 trace has no vote
+    assert oracle.weighted_vote(np.array([5, 2], np.int32), np.array([0.5, 0.5], np.float32)) == (2, 0.5)  # tie
+    assert oracle.weighted_vote(np.array([-1, -1], np.int32), np.array([0.5, 0.5], np.float32))[0] == -1
+    assert oracle.weighted_vote(np.zeros(0, np.int32), np.zeros(0, np.float32))[0] == -1
+    # one confident trace outweighs two weak ones: majority by weight, not by count
+    assert oracle.weighted_vote(np.array([1, 1, 2], np.int32), np.array([0.2, 0.2, 0.9], np.float32))[0] == 2
+
+
+def test_weighted_vote_matches_dictionary_accumulation():
+    r = wl.rng_for(10, 0)
+    for _ in range(20):
+        N = int(r.integers(1, 60))
+        a = r.integers(-1, 6, N).astype(np.int32)
+        s = r.uniform(0, 1, N).astype(np.float32)
+        tot = {}
+        for i in range(N):
+            if a[i] >= 0:
+                tot[int(a[i])] = np.float32(tot.get(int(a[i]), np.float32(0)) + s[i])
+        w, wt = oracle.weighted_vote(a, s)
+        if not tot:
+            assert w == -1
+        else:
+            best = min(tot, key=lambda key: (-tot[key], key))
+            assert (w, np.float32(wt)) == (best, tot[best])
