@@ -1,7 +1,8 @@
 /*
  * libstep -- C ABI of the decode-step hot path of STEP (arxiv 2601.09093) on one MI355X (gfx950).
  *
- * One decode step over N parallel reasoning traces of one prompt is three calls, in this order:
+ * One decode step over N parallel reasoning traces of one prompt is three hot calls, in this order
+ * (step_reserve_pages / step_append_kv / step_weighted_vote further down complete Algorithm 1):
  *   paged_decode_attn   the attention inside NextToken(t) of Algorithm 1, for all live traces,
  *   step_score          y = f(h) for the traces at a step boundary, then "Update score_t"
  *                       (Section 4.1 equation; Section 4.3 running average),
@@ -174,6 +175,57 @@ int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scor
                int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
                int32_t *freed_pages, int32_t *n_freed, void *workspace, size_t workspace_bytes,
                int32_t *status, void *stream);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Memory-triggered pruning + page allocation (Section 4.2; the GPUMemoryFull branch of         */
+/* Algorithm 1), the KV-cache write of NextToken, and WeightedVote (Section 4.3).               */
+/* With these a multi-step decode loop runs on the device with no host round trip:              */
+/*   step_reserve_pages -> step_append_kv -> paged_decode_attn -> step_score                    */
+/* ------------------------------------------------------------------------------------------ */
+
+size_t step_reserve_workspace_bytes(int32_t N, int32_t MAXB, int32_t NP);
+
+/*
+ * Before the next decode step: a live trace with seq_lens[i] % P == 0 needs a new page for its next
+ * token.  While fewer pages are free (refcount 0) than traces need one, the live trace with the
+ * smallest (scores[i], i) is pruned exactly as prune_free prunes one trace (pages released, row set
+ * to -1, seq_len 0) -- "whenever GPU memory is full and the KV cache for the next decoding step
+ * cannot be scheduled, prune the trace with the lowest average step score".  Then every trace that
+ * still needs a page, in ascending index, takes the smallest free page id:
+ * block_tables[i][seq_lens[i] / P] = page, refcounts[page] = 1, new_pages[i] = page.
+ *
+ *   scores [N] fp32 | refcounts [NP], block_tables [N][MAXB], seq_lens [N] int32 in/out
+ *   pruned [N] int32 out (first *n_pruned entries, pruning order) | n_pruned [1] int32 out
+ *   new_pages [N] int32 out (-1 where no page was given) | workspace >= step_reserve_workspace_bytes
+ * Device-reported errors: STEP_ELEN (bad length, or a trace on a page boundary whose row is full),
+ * STEP_ENAN (pruning needed and a live score is NaN) -- both before anything is modified;
+ * STEP_EPAGE / STEP_EREFCOUNT while releasing (that entry is skipped).  N <= 4096.
+ */
+int step_reserve_pages(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores,
+                       int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
+                       int32_t *n_pruned, int32_t *new_pages, void *workspace, size_t workspace_bytes,
+                       int32_t *status, void *stream);
+
+/*
+ * For every live trace i (L = seq_lens[i] > 0): the K and V rows of its newest token,
+ * k_new[i][g][:], v_new[i][g][:], are written to page block_tables[i][L / P], slot L % P, of every
+ * KV head g, and seq_lens[i] becomes L + 1.  dims: N, Hkv, D (multiple of 8), P = 16, MAXB, NP are
+ * used.  k_new, v_new [N][Hkv][D] bf16, 16-byte aligned.  refcounts may be NULL; when given, a
+ * target page with refcount != 1 is refused (STEP_EREFCOUNT): a shared page is never written.
+ * Device-reported errors skip that trace: STEP_ELEN (row full), STEP_EPAGE, STEP_EREFCOUNT.
+ */
+int step_append_kv(const step_attn_dims *dims, const uint16_t *k_new, const uint16_t *v_new,
+                   uint16_t *k_pages, uint16_t *v_pages, const int32_t *block_tables,
+                   const int32_t *refcounts, int32_t *seq_lens, int32_t *status, void *stream);
+
+/*
+ * answer[i] >= 0 is the final answer id of trace i, -1 means it has none (pruned, unfinished).  The
+ * weight of an answer is the fp32 sum, in trace index order, of scores[j] over the traces that gave
+ * it; *winner is the answer with the largest weight (ties: smallest id; -1 if nobody answered) and
+ * *weight its weight.  STEP_ENAN if a voting trace's score is NaN.  N <= 4096.
+ */
+int step_weighted_vote(int32_t N, const int32_t *answer, const float *scores, int32_t *winner,
+                       float *weight, int32_t *status, void *stream);
 
 /* ------------------------------------------------------------------------------------------ */
 /* Measurement aid: a plain copy kernel of known size (dst[i] = src[i], 16-byte units), used   */

@@ -69,6 +69,14 @@ def lib():
     L.step_prune_workspace_bytes.argtypes = [i32, i32, i32]
     L.prune_free.restype = ctypes.c_int
     L.prune_free.argtypes = [i32, i32, i32, i32, vp, i32] + [vp] * 7 + [sz, vp, vp]
+    L.step_reserve_workspace_bytes.restype = sz
+    L.step_reserve_workspace_bytes.argtypes = [i32, i32, i32]
+    L.step_reserve_pages.restype = ctypes.c_int
+    L.step_reserve_pages.argtypes = [i32, i32, i32, i32] + [vp] * 8 + [sz, vp, vp]
+    L.step_append_kv.restype = ctypes.c_int
+    L.step_append_kv.argtypes = [ctypes.POINTER(AttnDims)] + [vp] * 9
+    L.step_weighted_vote.restype = ctypes.c_int
+    L.step_weighted_vote.argtypes = [i32] + [vp] * 6
     L.step_calib_copy.restype = ctypes.c_int
     L.step_calib_copy.argtypes = [vp, vp, sz, vp]
     L.step_attn_profile_begin.restype = ctypes.c_int
@@ -225,6 +233,60 @@ def prune_free(scores, k, refcounts, block_tables, seq_lens, pruned=None, freed_
     if rc != STEP_OK:
         raise StepError(rc, "prune_free")
     return pruned, freed_pages, n_freed
+
+
+def reserve_pages(scores, refcounts, block_tables, seq_lens, pruned=None, n_pruned=None, new_pages=None,
+                  workspace=None, status=None, P=16):
+    """Memory-triggered pruning + allocation in place; returns (pruned [N], n_pruned [1], new_pages [N])."""
+    N, MAXB = block_tables.shape
+    NP = refcounts.numel()
+    dev = scores.device
+    i32 = (torch.int32,)
+    if pruned is None:
+        pruned = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
+    if n_pruned is None:
+        n_pruned = torch.empty(1, dtype=torch.int32, device=dev)
+    if new_pages is None:
+        new_pages = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(int(lib().step_reserve_workspace_bytes(N, MAXB, NP)), dev)
+    rc = lib().step_reserve_pages(
+        N, MAXB, NP, int(P), _dev(scores, (torch.float32,), "scores"), _dev(refcounts, i32, "refcounts"),
+        _dev(block_tables, i32, "block_tables"), _dev(seq_lens, i32, "seq_lens"), _dev(pruned, i32, "pruned"),
+        _dev(n_pruned, i32, "n_pruned"), _dev(new_pages, i32, "new_pages"),
+        _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _dev(status, i32, "status", True), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "step_reserve_pages")
+    return pruned, n_pruned, new_pages
+
+
+def append_kv(k_new, v_new, k_pages, v_pages, block_tables, seq_lens, refcounts=None, status=None):
+    """Write the newest token's K/V rows of every live trace into its page; seq_lens += 1 (in place)."""
+    N, Hkv, D = k_new.shape
+    NP, _, P, _ = k_pages.shape
+    dims = AttnDims(N, Hkv, Hkv, D, P, block_tables.shape[1], NP, 1.0)
+    i32 = (torch.int32,)
+    rc = lib().step_append_kv(
+        ctypes.byref(dims), _dev(k_new, _BF16_OK, "k_new"), _dev(v_new, _BF16_OK, "v_new"),
+        _dev(k_pages, _BF16_OK, "k_pages"), _dev(v_pages, _BF16_OK, "v_pages"),
+        _dev(block_tables, i32, "block_tables"), _dev(refcounts, i32, "refcounts", True),
+        _dev(seq_lens, i32, "seq_lens"), _dev(status, i32, "status", True), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "step_append_kv")
+
+
+def weighted_vote(answer, scores, status=None):
+    """Returns (winner [1] int32, weight [1] fp32) device tensors."""
+    dev = scores.device
+    winner = torch.empty(1, dtype=torch.int32, device=dev)
+    weight = torch.empty(1, dtype=torch.float32, device=dev)
+    rc = lib().step_weighted_vote(
+        answer.numel(), _dev(answer, (torch.int32,), "answer"), _dev(scores, (torch.float32,), "scores"),
+        _dev(winner, (torch.int32,), "winner"), _dev(weight, (torch.float32,), "weight"),
+        _dev(status, (torch.int32,), "status", True), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "step_weighted_vote")
+    return winner, weight
 
 
 def calib_copy(dst, src):

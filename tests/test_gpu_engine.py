@@ -1,0 +1,192 @@
+"""GPU parity of the pieces that complete Algorithm 1 around the three hot calls: memory-triggered
+pruning + page allocation (Section 4.2), KV append, weighted vote (Section 4.3), and a multi-step
+decode loop that runs entirely on the device."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_09093_amd import binding, workloads as wl
+from tests.gpu_util import DEV, dev, dev_bits, host_bits, host_f32_of_bf16, new_status
+
+pytestmark = pytest.mark.gpu
+P = 16
+
+
+def gpu_reserve(scores, rc, bt, sl, expect_status=0):
+    st = new_status()
+    t_rc, t_bt, t_sl = dev(rc.copy()), dev(bt.copy()), dev(sl.copy())
+    pruned, n_pruned, new_pages = binding.reserve_pages(dev(scores), t_rc, t_bt, t_sl, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == expect_status, binding.ERROR_NAMES.get(int(st.item()))
+    n = int(n_pruned.item())
+    return pruned.cpu().numpy()[:n], new_pages.cpu().numpy()[: sl.size], t_rc.cpu().numpy(), t_bt.cpu().numpy(), t_sl.cpu().numpy()
+
+
+def check_reserve(scores, rc, bt, sl):
+    got = gpu_reserve(scores, rc, bt, sl)
+    o_rc, o_bt, o_sl = rc.copy(), bt.copy(), sl.copy()
+    o_pruned, o_new = oracle.reserve_pages(scores, o_rc, o_bt, o_sl, P)
+    for name, a, b in zip(("pruned", "new_pages", "refcounts", "block_tables", "seq_lens"), got,
+                          (o_pruned, o_new, o_rc, o_bt, o_sl)):
+        assert np.array_equal(a, b), name
+    return got
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_reserve_pages_random_layouts(seed):
+    r = wl.rng_for(700 + seed, 0)
+    N = int(r.integers(1, 70))
+    lens = 32 + 16 * r.integers(0, 6, N) + np.where(r.random(N) < 0.5, 0, r.integers(1, 16, N))
+    lens[r.random(N) < 0.1] = 0
+    lay = wl.build_layout(lens, 32, P, wl.rng_for(700 + seed, 1), slack=1.0, maxb=12)
+    extra = int(r.integers(0, max(N // 2, 1)))
+    rc = np.concatenate([lay.refcounts, np.zeros(extra, np.int32)])
+    perm = wl.rng_for(700 + seed, 2).permutation(rc.size)            # scatter the free pages
+    rc2 = np.empty_like(rc); rc2[perm] = rc
+    bt = np.where(lay.block_tables >= 0, perm[np.maximum(lay.block_tables, 0)], -1).astype(np.int32)
+    scores = (r.integers(0, 20, N) / 16.0).astype(np.float32)        # ties
+    check_reserve(scores, rc2, bt, lay.seq_lens)
+
+
+def test_reserve_pages_hand_example_and_no_pressure():
+    lay = wl.build_layout(np.array([32, 32, 32, 32]), 0, P, wl.rng_for(2, 1), maxb=4)
+    pruned, new, rc, bt, sl = check_reserve(np.array([0.2, 0.7, 0.1, 0.9], np.float32), lay.refcounts,
+                                            lay.block_tables, lay.seq_lens)
+    assert pruned.tolist() == [2, 0] and sl.tolist() == [0, 32, 0, 32]
+    rc_big = np.concatenate([lay.refcounts, np.zeros(10, np.int32)])
+    pruned, new, *_ = check_reserve(np.zeros(4, np.float32), rc_big, lay.block_tables, lay.seq_lens)
+    assert pruned.size == 0 and new.tolist() == [8, 9, 10, 11]
+
+
+def test_reserve_pages_config5_scale_saturated_pool():
+    """N = 256 traces over a pool filled to capacity: the step that follows needs ~16 pages."""
+    w = wl.make_workload(5, kv=False)
+    lay = w.layout
+    sl = lay.seq_lens.copy()
+    sl[::9] = (sl[::9] // P) * P                                      # put some traces on a page boundary
+    bt = lay.block_tables.copy()
+    rc = lay.refcounts.copy()
+    for i in range(0, 256, 9):                                        # drop the pages past the shortened length
+        nb_new = sl[i] // P
+        extra = bt[i, nb_new:][bt[i, nb_new:] >= 0]
+        rc[extra] -= 1
+        bt[i, nb_new:] = -1
+    scores = (w.scorer.score_sum / w.scorer.score_cnt).astype(np.float32)
+    pruned, new, *_ = check_reserve(scores, rc, bt, sl)
+    assert (new >= 0).sum() > 0
+
+
+def test_reserve_pages_errors():
+    lay = wl.build_layout(np.array([32, 32]), 0, P, wl.rng_for(4, 1), maxb=2)
+    gpu_reserve(np.zeros(2, np.float32), lay.refcounts, lay.block_tables, lay.seq_lens, expect_status=17)
+    lay = wl.build_layout(np.array([32, 32]), 0, P, wl.rng_for(5, 1), maxb=4)
+    got = gpu_reserve(np.array([np.nan, 0.5], np.float32), lay.refcounts, lay.block_tables, lay.seq_lens,
+                      expect_status=19)
+    assert np.array_equal(got[2], lay.refcounts) and np.array_equal(got[3], lay.block_tables)
+
+
+def test_append_kv_bit_exact():
+    lay = wl.build_layout(np.array([17, 32, 0, 5, 100, 48]), 0, P, wl.rng_for(6, 1), slack=1.5, maxb=8)
+    Hkv, D = 8, 128
+    NP = lay.NP + 2
+    k = wl.normal_bf16(wl.rng_for(6, 2), (NP, Hkv, P, D)); v = wl.normal_bf16(wl.rng_for(6, 3), k.shape)
+    rc = np.concatenate([lay.refcounts, [1, 1]]).astype(np.int32)
+    bt = lay.block_tables.copy(); bt[1, 2] = lay.NP; bt[5, 3] = lay.NP + 1
+    kn = wl.normal_bf16(wl.rng_for(6, 4), (6, Hkv, D)); vn = wl.normal_bf16(wl.rng_for(6, 5), (6, Hkv, D))
+    tk, tv, tsl = dev_bits(k), dev_bits(v), dev(lay.seq_lens.copy())
+    st = new_status()
+    binding.append_kv(dev_bits(kn), dev_bits(vn), tk, tv, dev(bt), tsl, refcounts=dev(rc), status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    sl = lay.seq_lens.copy()
+    oracle.append_kv(kn, vn, k, v, bt, rc, sl)
+    assert np.array_equal(host_bits(tk), k) and np.array_equal(host_bits(tv), v)
+    assert np.array_equal(tsl.cpu().numpy(), sl)
+
+
+def test_append_kv_errors():
+    lay = wl.build_layout(np.array([16, 20]), 0, P, wl.rng_for(8, 1), maxb=2)
+    k = np.zeros((lay.NP, 1, P, 64), np.uint16)
+    kn = np.ones((2, 1, 64), np.uint16)
+    st = new_status()
+    tsl = dev(lay.seq_lens.copy())
+    binding.append_kv(dev_bits(kn), dev_bits(kn), dev_bits(k), dev_bits(k), dev(lay.block_tables), tsl, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 16 and tsl.cpu().numpy().tolist() == [16, 21]     # trace 0 refused, trace 1 appended
+
+
+def test_weighted_vote_bit_exact():
+    r = wl.rng_for(10, 0)
+    for N in (1, 6, 64, 257, 1000):
+        a = r.integers(-1, 7, N).astype(np.int32)
+        s = r.uniform(0, 1, N).astype(np.float32)
+        st = new_status()
+        w, wt = binding.weighted_vote(dev(a), dev(s), status=st)
+        torch.cuda.synchronize()
+        ow, owt = oracle.weighted_vote(a, s)
+        assert int(st.item()) == 0 and int(w.item()) == ow and np.float32(wt.item()) == np.float32(owt)
+    w, _ = binding.weighted_vote(dev(np.full(5, -1, np.int32)), dev(np.ones(5, np.float32)))
+    assert int(w.item()) == -1
+
+
+def test_multi_step_decode_loop_on_device():
+    """150 decode steps of 8 traces that share a 2-page prompt, in a pool too small for all of them:
+    reserve (memory-triggered pruning + allocation) -> append -> attention -> scorer -> running mean,
+    every step on the device; the oracle replays the same steps (fed the GPU's step probabilities,
+    so that the scores are the same bytes) and every integer state must match bit for bit."""
+    N, Hq, Hkv, D, d, m = 8, 4, 1, 64, 256, 64
+    steps, NP, MAXB = 150, 44, 16
+    r = wl.rng_for(77, 0)
+    lay = wl.build_layout(np.full(N, 32), 32, P, wl.rng_for(77, 1), slack=1.0, maxb=MAXB)
+    rc = np.concatenate([lay.refcounts, np.zeros(NP - lay.NP, np.int32)])
+    bt, sl = lay.block_tables.copy(), lay.seq_lens.copy()
+    k = wl.normal_bf16(wl.rng_for(77, 2), (NP, Hkv, P, D)); v = wl.normal_bf16(wl.rng_for(77, 3), k.shape)
+    sc = wl.build_scorer(77, N, N, d, m, 0, 0)
+    ssum, cnt = np.zeros(N, np.float32), np.zeros(N, np.int32)
+    scores = np.full(N, np.inf, np.float32)
+
+    t_rc, t_bt, t_sl = dev(rc), dev(bt), dev(sl)
+    t_k, t_v = dev_bits(k), dev_bits(v)
+    t_sum, t_cnt, t_scores = dev(ssum), dev(cnt), dev(scores)
+    t_W1, t_b1, t_W2 = dev_bits(sc.W1), dev(sc.b1), dev_bits(sc.W2)
+    t_b2 = torch.tensor([sc.b2], dtype=torch.float32, device=DEV)
+    st = new_status()
+    total_pruned = 0
+    for step in range(steps):
+        kn = wl.normal_bf16(wl.rng_for(1000 + step, 0), (N, Hkv, D)); vn = wl.normal_bf16(wl.rng_for(1000 + step, 1), (N, Hkv, D))
+        q = wl.normal_bf16(wl.rng_for(1000 + step, 2), (N, Hq, D))
+        hidden = wl.normal_bf16(wl.rng_for(1000 + step, 3), (N, d))
+        live = np.nonzero(sl > 0)[0]
+        if live.size == 0:
+            break
+        bidx = live[wl.rng_for(1000 + step, 4).random(live.size) < 0.3].astype(np.int32)
+        # device
+        pruned, n_pruned, new_pages = binding.reserve_pages(t_scores, t_rc, t_bt, t_sl, status=st)
+        binding.append_kv(dev_bits(kn), dev_bits(vn), t_k, t_v, t_bt, t_sl, refcounts=t_rc, status=st)
+        out = binding.paged_decode_attn(dev_bits(q), t_k, t_v, t_bt, t_sl, status=st)
+        logits, probs = binding.step_score(dev_bits(hidden), dev(bidx), t_W1, t_b1, t_W2, t_b2, trace_of=dev(bidx),
+                                           score_sum=t_sum, score_cnt=t_cnt, scores=t_scores, status=st)
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0, (step, binding.ERROR_NAMES.get(int(st.item())))
+        # oracle replay
+        o_pruned, o_new = oracle.reserve_pages(scores, rc, bt, sl, P)
+        oracle.append_kv(kn, vn, k, v, bt, rc, sl)
+        o_out = oracle.paged_decode_attn(q, k, v, bt, sl)
+        o_logits, _ = oracle.step_score(hidden, bidx, sc.W1, sc.b1, sc.W2, sc.b2)
+        scores = oracle.running_mean(bidx, probs.cpu().numpy(), ssum, cnt)
+        n = int(n_pruned.item())
+        total_pruned += n
+        assert pruned.cpu().numpy()[:n].tolist() == o_pruned.tolist(), step
+        assert np.array_equal(new_pages.cpu().numpy()[:N], o_new), step
+        assert np.array_equal(t_rc.cpu().numpy(), rc) and np.array_equal(t_bt.cpu().numpy(), bt), step
+        assert np.array_equal(t_sl.cpu().numpy(), sl) and np.array_equal(t_scores.cpu().numpy(), scores), step
+        assert np.abs(host_f32_of_bf16(out) - o_out).max() <= 2e-2, step
+        if bidx.size:
+            assert np.abs(logits.cpu().numpy() - o_logits).max() <= 1e-3, step
+    assert np.array_equal(host_bits(t_k), k) and np.array_equal(host_bits(t_v), v)
+    assert total_pruned >= 3 and (sl > 0).sum() >= 1          # the pool forced pruning, and no step failed to allocate
+    # the survivors vote
+    answers = np.where(sl > 0, np.arange(N) % 3, -1).astype(np.int32)
+    w, wt = binding.weighted_vote(dev(answers), t_scores)
+    assert (int(w.item()), np.float32(wt.item())) == tuple(map(lambda x: x, (oracle.weighted_vote(answers, scores)[0], np.float32(oracle.weighted_vote(answers, scores)[1]))))
