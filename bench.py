@@ -36,6 +36,12 @@ def parse_args():
     ap.add_argument("--prune-k", type=int, default=None, help="traces pruned per step (default 1; config 5: 64)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=["step", "loop"], default="step",
+                    help="step: attention + scorer + prune_free(k) on a fresh copy of the state every step (default); "
+                         "loop: Algorithm 1's decode loop on one evolving state: reserve pages (memory-triggered "
+                         "pruning) + KV append + attention + scorer")
+    ap.add_argument("--free-pages", type=int, default=16,
+                    help="loop mode: free pages left in the pool at the start (the rest is marked occupied)")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="only run libstep's plain copy kernel on MIB MiB (profiler byte-counter calibration)")
     return ap.parse_args()
@@ -166,6 +172,33 @@ def main():
         binding.prune_free(scores, prune_k, rc_s[i], bt_s[i], sl_s[i], pruned=pruned, freed_pages=freed,
                            n_freed=n_freed, workspace=ws_prune, status=status)
 
+    if args.mode == "loop":
+        # one evolving state; the pool is nearly full so that the memory trigger fires inside the run
+        rc_np = lay.refcounts.copy()
+        free_ids = np.nonzero(rc_np == 0)[0]
+        rc_np[free_ids[args.free_pages:]] = 1                       # occupied by someone else
+        rc_l, bt_l, sl_l = t(rc_np), t(lay.block_tables), t(lay.seq_lens)
+        sum_l, cnt_l = t(sum0), t(cnt0)
+        scores.copy_(t((sum0 / cnt0).astype(np.float32)))
+        k_new = torch.randn((s.N, s.Hkv, s.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        v_new = torch.randn((s.N, s.Hkv, s.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        pruned_l = torch.empty(s.N, dtype=torch.int32, device=dev)
+        n_pruned_l = torch.zeros(1, dtype=torch.int32, device=dev)
+        new_pages_l = torch.empty(s.N, dtype=torch.int32, device=dev)
+        ws_res = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(s.N, lay.MAXB, lay.NP)), dev)
+        pruned_total = torch.zeros(1, dtype=torch.int32, device=dev)
+
+        def step(i):  # noqa: F811  (replaces the per-copy step above)
+            binding.reserve_pages(scores, rc_l, bt_l, sl_l, pruned=pruned_l, n_pruned=n_pruned_l,
+                                  new_pages=new_pages_l, workspace=ws_res, status=status)
+            pruned_total.add_(n_pruned_l)
+            binding.append_kv(k_new, v_new, k_pages, v_pages, bt_l, sl_l, refcounts=rc_l, status=status)
+            binding.paged_decode_attn(q, k_pages, v_pages, bt_l, sl_l, out=out, workspace=ws_attn, status=status)
+            binding.step_score(hidden, bidx, W1, b1, W2, b2, act=sc.act, logits=logits, probs=probs,
+                               trace_of=trace_of, score_sum=sum_l, score_cnt=cnt_l, scores=scores,
+                               workspace=ws_score, status=status)
+        n_freed.fill_(1)
+
     # state copies: W warm-up steps, K timed steps, K more steps with stage 1 bracketed by events
     for i in range(W):
         step(i)
@@ -199,11 +232,11 @@ def main():
                  + items * G * (s.D + 2) * 4)                       # split-K partials written by stage 1
     avg_ms = float(np.mean(stage1_ms))
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
-    workload = "config%d" % args.config
+    workload = "config%d" % args.config + ("-loop" if args.mode == "loop" else "")
     roofline = {
         "kernel": "attn_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": traffic_from_profiles("attn_partial", workload),
+        "traffic": traffic_from_profiles("attn_partial", "config%d" % args.config),
         "algorithmic_bytes": int(alg_bytes), "avg_kernel_ms": round(avg_ms, 4),
         "min_kernel_ms": round(float(np.min(stage1_ms)), 4), "launches": len(stage1_ms),
     }
@@ -218,12 +251,16 @@ def main():
                    "unique_kv_tokens": lay.unique_tokens, "pool_pages": lay.NP, "scorer": "%d->%d->1 %s, B=%d" % (
                        sc.hidden.shape[1], sc.W1.shape[0], "ReLU" if sc.act == 0 else "GELU", B),
                    "prune_k": prune_k, "attn_waves_per_kv_head": binding.attn_waves_per_head(adims),
-                   "attn_records": records},
+                   "attn_records": records, "mode": args.mode},
         "attn_hbm_gbs": round(achieved, 1), "attn_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "roofline": roofline,
     }
 
-    if not args.no_cpu_baseline:
+    if args.mode == "loop":
+        result["config"]["traces_pruned_by_memory_trigger"] = int(pruned_total.item())
+        result["config"]["live_traces_at_end"] = int((sl_l > 0).sum().item())
+        result["config"]["free_pages_at_start"] = args.free_pages
+    if not args.no_cpu_baseline and args.mode == "step":
         result["cpu_baseline"] = cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k, layers)
     print(json.dumps(result))
 

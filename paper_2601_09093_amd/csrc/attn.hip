@@ -170,12 +170,15 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         __syncthreads();
         const int32_t *row0 = a.block_tables + (size_t)live_list[0] * a.MAXB;
         int first_diff = cap;  // smallest page index at which some live row differs from the first live row
-        // consecutive lanes compare consecutive entries of one row (coalesced), four loads in flight
+        // consecutive lanes compare consecutive entries of one row (coalesced); the planner runs
+        // right after gigabytes were streamed through every cache, so all of a thread's loads are
+        // issued before the first compare (16 pairs in flight per thread)
+        constexpr int kBatch = 16;
         const int work = (n_live - 1) * cap;
-        for (int base = 0; base < work; base += 4 * kPlanThreads) {
-            int x[4], y[4], jj[4];
+        for (int base = 0; base < work; base += kBatch * kPlanThreads) {
+            int x[kBatch], y[kBatch], jj[kBatch];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kBatch; ++u) {
                 const int idx = min(base + u * kPlanThreads + tid, work - 1);
                 const int rk = 1 + idx / cap;
                 jj[u] = idx % cap;
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
                 y[u] = row0[jj[u]];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < kBatch; ++u)
                 if (x[u] != y[u]) first_diff = min(first_diff, jj[u]);
         }
 #pragma unroll

@@ -103,16 +103,47 @@ __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveAr
         lens[i] = keep;
         a.new_pages[i] = -1;
     }
-    // free-page bitmap from the refcounts: one page per lane, one 64-bit ballot per wave
+    // free-page bitmap from the refcounts.  The scan runs right after the attention kernel has
+    // streamed gigabytes through every cache, so each dependent round trip is a cold one: all loads
+    // of a thread are issued before the first is used (four pages per 16-byte load, 16 loads
+    // in flight), eight neighbouring lanes then assemble one 32-bit word of the bitmap.
     int my_free = 0;
-    for (int base = 0; base < a.words * 32; base += kThreads) {
-        const int p = base + tid;
-        const bool is_free = p < a.NP && a.refcounts[p] == 0;
-        const u64 mask = __ballot(is_free);
-        if (lane == 0) {
-            a.bitmap[(p >> 5)] = (u32)mask;
-            a.bitmap[(p >> 5) + 1] = (u32)(mask >> 32);
-            my_free += __popcll(mask);
+    {
+        constexpr int kBatch = 16;
+        const int quads = a.words * 8;  // groups of four pages
+        const bool vec_ok = (reinterpret_cast<uintptr_t>(a.refcounts) & 15) == 0;
+        for (int base = 0; base < quads; base += kBatch * kThreads) {
+            int4 v[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int qd = base + u * kThreads + tid;
+                const int p = qd * 4;
+                v[u] = make_int4(1, 1, 1, 1);
+                if (qd < quads) {
+                    if (vec_ok && p + 3 < a.NP) {
+                        v[u] = *reinterpret_cast<const int4 *>(a.refcounts + p);
+                    } else {
+                        if (p + 0 < a.NP) v[u].x = a.refcounts[p + 0];
+                        if (p + 1 < a.NP) v[u].y = a.refcounts[p + 1];
+                        if (p + 2 < a.NP) v[u].z = a.refcounts[p + 2];
+                        if (p + 3 < a.NP) v[u].w = a.refcounts[p + 3];
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int qd = base + u * kThreads + tid;
+                u32 nib = (v[u].x == 0 ? 1u : 0u) | (v[u].y == 0 ? 2u : 0u) | (v[u].z == 0 ? 4u : 0u) |
+                          (v[u].w == 0 ? 8u : 0u);
+                u32 word = nib << (4 * (lane & 7));
+                word |= __shfl_xor(word, 1);
+                word |= __shfl_xor(word, 2);
+                word |= __shfl_xor(word, 4);
+                if ((lane & 7) == 0 && qd < quads) {
+                    a.bitmap[qd >> 3] = word;
+                    my_free += __popc(word);
+                }
+            }
         }
     }
     int needed = block_sum(my_need, scratch);
