@@ -520,9 +520,16 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         bad_page |= !ok;
         return ((size_t)(ok ? page : 0) * a.Hkv + g) * tile_u4 + lane;
     };
+    // KV tiles are read once and never again by this wave: non-temporal loads (streaming cache
+    // policy) keep them from displacing each other in the caches; measured +10 % on a bare tile
+    // stream, and the shared prompt tiles are still served from L2
     auto load4 = [&](const uint4 *base, size_t off, uint4 (&x)[IPP]) {
+        typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-        for (int j = 0; j < IPP; ++j) x[j] = base[off + j * 64];
+        for (int j = 0; j < IPP; ++j) {
+            const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + off + j * 64));
+            x[j] = make_uint4(t.x, t.y, t.z, t.w);
+        }
     };
 
     uint4 qv[G];
@@ -861,7 +868,7 @@ int waves_per_head(const step_attn_dims *d)
         int nblk = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, attn_partial_g4<128>, 64, 0) != hipSuccess || nblk <= 0)
             nblk = 8;
-        return nblk < 8 ? nblk : 8;  // measured: more than 8 resident waves per CU do not stream faster
+        return nblk < 4 ? nblk : 4;  // measured: one wave per SIMD streams fastest (no ALU contention between waves)
     }();
     const int per_cu = per_cu_env > 0 ? per_cu_env : per_cu_128;
     int wh = cus * per_cu / d->Hkv;
