@@ -235,9 +235,10 @@ int step_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------ */
 /* Measurement aid: per-kernel timing of attention's stage 1 (the HBM-streaming kernel).       */
-/* After step_attn_profile_begin(cap), each paged_decode_attn call brackets its stage-1 kernel */
-/* with two HIP events from a pool of `cap` pairs created by that call, on the stream it       */
-/* launches on (calls beyond `cap` are not bracketed).  step_attn_profile_end waits for the    */
+/* After step_attn_profile_begin(cap), each paged_decode_attn call attaches two HIP events from */
+/* a pool of `cap` pairs created by that call to its stage-1 kernel launch (they take the       */
+/* kernel's begin and end timestamps on the stream it launches on; calls beyond `cap` are not   */
+/* timed).  step_attn_profile_end waits for the                                                */
 /* recorded events, writes each bracketed call's stage-1 time in milliseconds to ms[0..n)      */
 /* (HOST array of capacity cap), destroys the pool and returns n, or -STEP_EINVAL.             */
 /* Benchmark use only: not thread safe, creates and destroys events.                           */

@@ -21,6 +21,8 @@
 //                store the current record's partial, so no load latency is exposed between records.
 //   attn_merge   stage 2: per (trace, query head) combine the record partials (m, l, acc), round to
 //                bf16.
+#include <hip/hip_ext.h>
+
 #include "common.h"
 
 namespace step {
@@ -914,13 +916,21 @@ int launch(const AttnArgs &a, hipStream_t s, int what)
 {
     if (what & kDoPlan) hipLaunchKernelGGL(attn_plan, dim3(1), dim3(kPlanThreads), 0, s, a);
     if (what & kDoAttend) {
+        // when profiling, the stage-1 launch carries its own start/stop events: they take the
+        // kernel's begin and end timestamps, with no marker processing inside the interval
         const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
-        if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], s);
-        if constexpr (G == 4)
-            hipLaunchKernelGGL((attn_partial_g4<D>), dim3((u32)(a.Wh * a.Hkv)), dim3(64), 0, s, a);
-        else
-            hipLaunchKernelGGL((attn_partial<D, G>), dim3((u32)(a.max_records * a.Hkv)), dim3(64), 0, s, a);
-        if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used++ + 1], s);
+        hipEvent_t e0 = timed ? g_prof.ev[2 * g_prof.used] : nullptr;
+        hipEvent_t e1 = timed ? g_prof.ev[2 * g_prof.used + 1] : nullptr;
+        if (timed) ++g_prof.used;
+        if constexpr (G == 4) {
+            const dim3 grid((u32)(a.Wh * a.Hkv));
+            if (timed) hipExtLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, e0, e1, 0, a);
+            else hipLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, a);
+        } else {
+            const dim3 grid((u32)(a.max_records * a.Hkv));
+            if (timed) hipExtLaunchKernelGGL((attn_partial<D, G>), grid, dim3(64), 0, s, e0, e1, 0, a);
+            else hipLaunchKernelGGL((attn_partial<D, G>), grid, dim3(64), 0, s, a);
+        }
         hipLaunchKernelGGL((attn_merge<D, G>), dim3((u32)(a.N * a.Hq)), dim3(64), 0, s, a);
     }
     return launch_status();
