@@ -41,7 +41,8 @@ enum step_error {
     STEP_EINDEX = 18,    /* device: boundary_idx outside [0, R) or trace_of outside [0, N)       */
     STEP_ENAN = 19,      /* device: NaN score on a live trace                                    */
     STEP_EREFCOUNT = 20, /* device: a released page had refcount <= 0                            */
-    STEP_EKLIVE = 21     /* device: k larger than the number of live traces                      */
+    STEP_EKLIVE = 21,    /* device: k larger than the number of live traces                      */
+    STEP_EPLAN = 22      /* device: the workspace holds no plan made for these dims              */
 };
 
 /* Human-readable name of an error code (host pointer to a static string). */

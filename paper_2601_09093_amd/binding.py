@@ -17,7 +17,7 @@ _lib = None
 STEP_OK = 0
 ERROR_NAMES = {
     0: "STEP_OK", 1: "STEP_EINVAL", 2: "STEP_EWORKSPACE", 3: "STEP_ELAUNCH", 16: "STEP_EPAGE",
-    17: "STEP_ELEN", 18: "STEP_EINDEX", 19: "STEP_ENAN", 20: "STEP_EREFCOUNT", 21: "STEP_EKLIVE",
+    17: "STEP_ELEN", 18: "STEP_EINDEX", 19: "STEP_ENAN", 20: "STEP_EREFCOUNT", 21: "STEP_EKLIVE", 22: "STEP_EPLAN",
 }
 ACT_RELU, ACT_GELU = 0, 1
 

@@ -49,7 +49,8 @@ struct PlanHeader {   // 256 bytes
     int32_t parts;    // sub-chunks of the shared prefix per trace (0 when nothing is shared)
     int32_t shared;   // S: leading pages common to every live trace
     int32_t quota;    // Q: pages per wave
-    int32_t pad[58];
+    int32_t stamp;    // hash of the dims the plan was made for (AttnArgs::stamp), never 0
+    int32_t pad[57];
 };
 
 struct AttnArgs {
@@ -66,6 +67,7 @@ struct AttnArgs {
     uint16_t *out;
     int32_t *status;
     int N, Hq, Hkv, MAXB, NP, Wh, max_records;
+    int stamp;            // what hdr->stamp must hold for this call's dims
     float scale_log2;     // scale * log2(e)
 };
 
@@ -289,7 +291,20 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         a.hdr->parts = parts;
         a.hdr->shared = S;
         a.hdr->quota = Q;
+        a.hdr->stamp = a.stamp;
     }
+}
+
+// A plan is trusted only if it was made for the same dims: the stamp guards against a workspace
+// that was never planned or was planned for another shape (garbage records would index out of the
+// block tables).  Returns false, and reports, when the plan in the workspace cannot be used.
+__device__ __forceinline__ bool plan_usable(const AttnArgs &a)
+{
+    const PlanHeader *h = a.hdr;
+    const bool ok = h->stamp == a.stamp && h->n1 >= 0 && h->total >= h->n1 && h->total <= a.max_records &&
+                    h->n_live >= 0 && h->n_live <= a.N && h->parts >= 0 && h->parts <= kMaxParts;
+    if (!ok && threadIdx.x == 0) report(a.status, STEP_EPLAN);
+    return ok;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -307,9 +322,14 @@ __global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
     const int r = lane / LPR, c = lane % LPR;
     const int g = blockIdx.x % a.Hkv;
     const int rec_id = blockIdx.x / a.Hkv;
-    if (rec_id >= a.hdr->total) return;
+    if (!plan_usable(a) || rec_id >= a.hdr->total) return;
     const Record rec = a.records[rec_id];
     const int i = rec.i, n = rec.n;
+    if ((u32)i >= (u32)a.N || rec.first < 0 || n < 1 || (long long)rec.first + n > a.MAXB || rec.ntok < 1 ||
+        rec.ntok > kPageTokens) {
+        if (lane == 0) report(a.status, STEP_EPLAN);
+        return;
+    }
 
     uint4 qv[G];
 #pragma unroll
@@ -494,8 +514,13 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     // records n1 + [off2[wh], off2[wh + 1]).
     const int g = blockIdx.x % a.Hkv;
     const int wh = blockIdx.x / a.Hkv;
+    if (!plan_usable(a)) return;
     const int n1 = a.hdr->n1;
     const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
+    if (p2_begin < n1 || p2_end < p2_begin || p2_end > a.hdr->total) {
+        if (lane == 0) report(a.status, STEP_EPLAN);
+        return;
+    }
     auto next_record = [&](int id) {  // id of the record after `id` in this wave's list, -1 at the end
         int nx;
         if (id < n1) {
@@ -631,8 +656,20 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
             if (jj * TPI + r >= ntok) v[jj] = make_uint4(0, 0, 0, 0);
     };
 
+    // a record that points outside the block tables (a workspace overwritten after planning) is
+    // replaced by a one-token record of trace 0 and reported; nothing is read out of bounds
+    bool bad_plan = false;
+    auto record_at = [&](int id) {
+        Record x = a.records[id];
+        const bool ok = (u32)x.i < (u32)a.N && x.first >= 0 && x.n >= 1 && (long long)x.first + x.n <= a.MAXB &&
+                        x.ntok >= 1 && x.ntok <= kPageTokens;
+        bad_plan |= !ok;
+        if (!ok) x = Record{0, 0, 1, 1};
+        return x;
+    };
+
     uint4 k0[IPP], v0[IPP], k1[IPP], v1[IPP];
-    Record rec = a.records[rec_id];
+    Record rec = record_at(rec_id);
     {
         const int32_t *bt0 = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
         const size_t t0 = tile_at(bt0[0]), t1 = tile_at(bt0[rec.n > 1 ? 1 : 0]);
@@ -648,7 +685,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         const bool has_next = next_id >= 0;
         // the next record and the ids of its first two pages are fetched now and consumed after this
         // record's pages
-        const Record nrec = a.records[has_next ? next_id : rec_id];
+        const Record nrec = record_at(has_next ? next_id : rec_id);
         const int32_t *nbt = a.block_tables + (size_t)nrec.i * a.MAXB + nrec.first;
         const int npage0 = nbt[0], npage1 = nbt[nrec.n > 1 ? 1 : 0];
 
@@ -755,6 +792,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         rec = nrec;
         rec_id = next_id;
     }
+    if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 
@@ -771,10 +809,15 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
     uint16_t *orow = a.out + ((size_t)i * a.Hq + h) * D;
     const int L = a.seq_lens[i];
     // the trace's records: `parts` shared-prefix sub-chunks, then cnt2 consecutive private ones
+    const bool usable = plan_usable(a);
     const int parts = a.hdr->parts, n_live = a.hdr->n_live;
     const int rk = a.rank[i], f2 = a.first2[i];
     int nch = parts + a.cnt2[i];
-    if (L <= 0 || (long long)L > (long long)a.MAXB * kPageTokens) nch = 0;
+    if (L <= 0 || (long long)L > (long long)a.MAXB * kPageTokens || !usable) nch = 0;
+    if (nch > 0 && ((u32)rk >= (u32)n_live || f2 < 0 || a.cnt2[i] < 0 || f2 + a.cnt2[i] > a.hdr->total)) {
+        if (lane == 0) report(a.status, STEP_EPLAN);
+        nch = 0;
+    }
     auto slot_of = [&](int ch) { return (size_t)(ch < parts ? ch * n_live + rk : f2 + (ch - parts)) * a.Hkv + g; };
 
     float o[DPT];
@@ -965,6 +1008,9 @@ int run(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages, con
     a.out = out; a.status = status;
     a.N = d->N; a.Hq = d->Hq; a.Hkv = d->Hkv; a.MAXB = d->MAXB; a.NP = d->NP;
     a.Wh = l.Wh; a.max_records = l.max_records;
+    // never 0, so a cleared workspace never passes for a plan
+    a.stamp = (int)((0x5157u ^ ((u32)d->N * 2654435761u) ^ ((u32)d->MAXB * 40503u) ^ ((u32)d->NP * 2246822519u) ^
+                     ((u32)d->Hkv << 24) ^ ((u32)l.Wh << 12)) | 1u);
     a.scale_log2 = d->scale * 1.4426950408889634f;
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

@@ -26,6 +26,7 @@ extern "C" const char *step_strerror(int code)
         case STEP_ENAN: return "STEP_ENAN: NaN score on a live trace";
         case STEP_EREFCOUNT: return "STEP_EREFCOUNT: released page had refcount <= 0";
         case STEP_EKLIVE: return "STEP_EKLIVE: k exceeds the number of live traces";
+        case STEP_EPLAN: return "STEP_EPLAN: the workspace holds no attention plan made for these dims";
     }
     return "unknown libstep error";
 }

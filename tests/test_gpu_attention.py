@@ -270,6 +270,38 @@ def test_one_plan_shared_by_several_layers():
         assert np.array_equal(host_bits(one), host_bits(outs[l]))
 
 
+@pytest.mark.parametrize("fill", [0, 0x7F, "other_dims"])
+def test_attend_without_a_matching_plan_is_reported_not_followed(fill):
+    """paged_decode_attn_planned on a workspace that holds no plan for these dims (cleared, garbage,
+    or planned for another block-table width) reports STEP_EPLAN and reads nothing the records name."""
+    lens = [40, 700, 33, 512, 90, 1500]
+    lay, q, k, v = build(77, lens, 8, 2, 128)
+    tq, tk, tv, bt, sl = dev_bits(q), dev_bits(k), dev_bits(v), dev(lay.block_tables), dev(lay.seq_lens)
+    nbytes = binding.attn_workspace_bytes(binding.AttnDims(len(lens), 8, 2, 128, P, lay.MAXB, lay.NP, 128 ** -0.5))
+    st = new_status()
+    if fill == "other_dims":
+        wide = np.concatenate([lay.block_tables, np.zeros_like(lay.block_tables)], axis=1)
+        nb2 = binding.attn_workspace_bytes(binding.AttnDims(len(lens), 8, 2, 128, P, wide.shape[1], lay.NP, 128 ** -0.5))
+        ws = binding.new_workspace(max(nbytes, nb2), DEV)
+        binding.attn_plan(tq, tk, dev(np.ascontiguousarray(wide)), sl, ws, status=st)
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0
+    else:
+        ws = torch.full((nbytes,), fill, dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(tq)
+    binding.paged_decode_attn_planned(tq, tk, tv, bt, sl, out, ws, status=st)
+    torch.cuda.synchronize()
+    assert binding.ERROR_NAMES[int(st.item())] == "STEP_EPLAN"
+    # the same workspace is good again once it has been planned for these dims
+    st.zero_()
+    binding.attn_plan(tq, tk, bt, sl, ws, status=st)
+    binding.paged_decode_attn_planned(tq, tk, tv, bt, sl, out, ws, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    want = oracle.paged_decode_attn(q, k, v, lay.block_tables, lay.seq_lens)
+    assert np.abs(host_f32_of_bf16(out) - want).max() <= TOL
+
+
 def test_config4_full_sweep_sampled_layers():
     """Config 4 at full size: 36 layers, N = 128 traces with lognormal lengths, ~210 GB of bf16 KV
     drawn on the device, one plan for the step, 36 attention calls; parity on layers 0, 17 and 35
