@@ -59,6 +59,13 @@ def test_all_head_shapes(D, G):
     check(q, k, v, lay.block_tables, lay.seq_lens)
 
 
+def test_forty_query_heads_over_ten_kv_heads():
+    """The 14B model of Section 5.1 has 40 query heads over 10 KV heads (the other two 32 over 8)."""
+    lens = 64 + wl.rng_for(140, 5).integers(1, 2500, 24)
+    lay, q, k, v = build(140, lens, 40, 10, 128, prompt=64)
+    check(q, k, v, lay.block_tables, lay.seq_lens)
+
+
 def test_ragged_edges_around_page_and_chunk_boundaries():
     lens = [0, 1, 2, 15, 16, 17, 31, 32, 33, 511, 512, 513, 527, 528, 529, 1023, 1024, 1025, 1537, 0, 2049]
     lay, q, k, v = build(7, lens, 8, 2, 128)
@@ -190,6 +197,35 @@ def test_planner_corner_cases(case):
     v = wl.normal_bf16(wl.rng_for(908, 3), (lay.NP, Hkv, P, D))
     wl.poison_unused(k, v, lay, P)
     check(q, k, v, lay.block_tables, lay.seq_lens)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_and_length_mixes(seed):
+    """Seeded sweep over head shapes (KV-head counts that do not divide the chip evenly included),
+    trace counts, dead traces, shared-prefix lengths, pool slack and row widths wider than needed."""
+    r = wl.rng_for(7000 + seed, 0)
+    D = int(r.choice([64, 128]))
+    G = int(r.choice([1, 2, 4, 4, 4, 8]))
+    Hkv = int(r.choice([1, 2, 3, 5, 8, 10]))
+    N = int(r.integers(1, 48))
+    prompt = int(r.choice([0, 0, 16, 48, 272])) if seed % 2 else int(r.choice([0, 1024]))
+    kind = r.integers(0, 4, N)
+    lens = np.where(kind == 0, r.integers(1, 20, N),
+                    np.where(kind == 1, r.integers(1, 600, N), r.integers(1, 3000, N))) + prompt
+    lens[r.random(N) < 0.15] = 0
+    nb_max = max(int((lens.max() + P - 1) // P), 1)
+    lay = wl.build_layout(lens, prompt, P, wl.rng_for(7000 + seed, 1), slack=float(r.choice([1.0, 1.3, 2.0])),
+                          maxb=nb_max + int(r.integers(0, 9)))
+    q = wl.normal_bf16(wl.rng_for(7000 + seed, 2), (N, G * Hkv, D), float(r.choice([0.5, 1.0, 2.0])))
+    k = wl.normal_bf16(wl.rng_for(7000 + seed, 3), (lay.NP, Hkv, P, D))
+    v = wl.normal_bf16(wl.rng_for(7000 + seed, 4), (lay.NP, Hkv, P, D))
+    wl.poison_unused(k, v, lay, P)
+    bt = lay.block_tables.copy()
+    nb = (lay.seq_lens.astype(np.int64) + P - 1) // P
+    for i in range(N):                                            # unused entries hold garbage, not -1
+        bt[i, nb[i]:] = r.integers(-5, 1 << 30, lay.MAXB - nb[i])
+    got, want = check(q, k, v, bt, lay.seq_lens)
+    assert np.all(got[lay.seq_lens == 0] == 0)
 
 
 def test_full_config2():
