@@ -2,23 +2,24 @@
 // KV cache -- the attention inside NextToken(t) of Algorithm 1 (the paper gives no formula; this
 // is softmax(q K^T scale) V for the newest token of every live trace).
 //
-// Three kernels per call:
-//   attn_plan    one workgroup.  Validates the lengths and cuts every live trace into records of at
-//                most CP pages (trace, first page, page count, tokens in the last page, ids of the
-//                first two pages).  Records are ordered: chunk 0 of every trace first (these cover
-//                a shared prompt, and running them at the same time turns N reads of the prompt's
-//                pages into one HBM read plus L2 hits), then the other full chunks, then the ragged
-//                last chunks (smallest work last).
-//   attn_partial stage 1, the HBM-streaming kernel.  One 64-lane wavefront per (record, KV head).
-//                A (page, head) tile is P*D bf16 contiguous; the wave reads it with 16-byte loads,
-//                lane l taking bytes [j*1024 + 16 l, +16) on load j, so every load instruction
-//                covers 1 KB of consecutive addresses.  A row of D values lives in LPR = D/8
-//                neighbouring lanes and each group of LPR lanes ("row group" r) sees the tokens
-//                r, r+TPI, ... of every page: TPI = 64/LPR independent online-softmax streams per
-//                wave, merged once per record.  The G query heads share every K and V register.
-//                For G == 4 the kernel is persistent: gridDim waves walk the record list with a
-//                fixed stride and start the next record's first tile loads before they reduce and
-//                store the current record's partial, so no load latency is exposed between records.
+// Four kernels per call:
+//   attn_plan    one workgroup.  Validates the lengths, finds the leading pages that every live trace
+//                shares (the prompt), and cuts the work into records (trace, first page, page count,
+//                tokens in the last page): the shared pages into sub-chunks, the private pages of all
+//                traces, concatenated, into one equal run per resident wave.
+//   attn_prefix  the shared pages on the matrix cores: for one KV head the query rows of all live
+//                traces form a dense matrix, so logits and output are two MFMA products and every
+//                shared tile is read once per block of query rows instead of once per trace.
+//   attn_partial stage 1, the HBM-streaming kernel over the private pages.  One 64-lane wavefront per
+//                (record, KV head).  A (page, head) tile is P*D bf16 contiguous; the wave reads it
+//                with 16-byte loads, lane l taking bytes [j*1024 + 16 l, +16) on load j, so every
+//                load instruction covers 1 KB of consecutive addresses.  A row of D values lives in
+//                LPR = D/8 neighbouring lanes and each group of LPR lanes ("row group" r) sees the
+//                tokens r, r+TPI, ... of every page: TPI = 64/LPR independent online-softmax streams
+//                per wave, merged once per record.  The G query heads share every K and V register.
+//                For G == 4 the kernel is persistent: each wave walks its own list of records and
+//                starts the next record's first tile loads before it reduces and stores the current
+//                record's partial, so no load latency is exposed between records.
 //   attn_merge   stage 2: per (trace, query head) combine the record partials (m, l, acc), round to
 //                bf16.
 #include <hip/hip_ext.h>
@@ -50,7 +51,9 @@ struct PlanHeader {   // 256 bytes
     int32_t shared;   // S: leading pages common to every live trace
     int32_t quota;    // Q: pages per wave
     int32_t stamp;    // hash of the dims the plan was made for (AttnArgs::stamp), never 0
-    int32_t pad[57];
+    int32_t part_pages; // pages per sub-chunk of the shared prefix (the last one may hold fewer)
+    int32_t prefix_mfma; // 1: the shared-prefix records are computed by attn_prefix, stage 1 skips them
+    int32_t pad[55];
 };
 
 struct AttnArgs {
@@ -62,24 +65,28 @@ struct AttnArgs {
     int32_t *rank;        // [N] rank of a live trace among the live traces
     int32_t *first2;      // [N] first record of the trace's private pages (they are consecutive)
     int32_t *cnt2;        // [N] number of such records
+    int32_t *live;        // [N] rank -> trace (the live traces in index order)
+    int32_t *shared_pages; // [kMaxShared] page ids of the shared prefix (read by attn_prefix)
     float *part_acc;      // [records * Hkv][G][D]   slot = record * Hkv + kv head
     float *part_ml;       // [records * Hkv][G][2]   (running max in log2 units, weight sum)
     uint16_t *out;
     int32_t *status;
     int N, Hq, Hkv, MAXB, NP, Wh, max_records;
     int stamp;            // what hdr->stamp must hold for this call's dims
+    int prefix_qt;        // 16-row query tiles per wave of attn_prefix (1 or 2); 0: no attn_prefix
     float scale_log2;     // scale * log2(e)
 };
 
 // ---------------------------------------------------------------------------------------------
 // plan: cut the work into records so that every one of the Wh waves of a KV head streams the same
 // number of pages (Q, give or take one).
-//   1. S = number of leading block-table entries that are identical in every live trace (the
-//      prompt's pages).  Those pages are cut into `parts` sub-chunks per trace and sub-chunk p of
-//      the trace of rank rk is record p * N_live + rk and goes to wave (p * N_live + rk) mod Wh,
-//      ahead of that wave's private pages: all
-//      waves start on the shared pages at the same time, so N reads of each shared tile become one
-//      HBM read plus L2 hits (all waves of one KV head run on one XCD when Hkv == 8).
+//   1. S = number of leading block-table entries that are identical in every live trace and lie
+//      below every live trace's last full page (the prompt's pages).  Those pages are cut into
+//      `parts` sub-chunks and sub-chunk p of the trace of rank rk is record p * N_live + rk.  With
+//      attn_prefix the sub-chunks are sized for its waves (whole page pairs, about one wave per SIMD)
+//      and stage 1 never sees these records.  Without it (testing aid) record s goes to wave s mod Wh
+//      ahead of that wave's private pages: all waves start on the shared pages at the same time, so
+//      N reads of each shared tile become one HBM read plus L2 hits.
 //   2. The private pages of all traces, concatenated trace by trace, are cut into Wh consecutive
 //      runs whose lengths top every wave up to Q pages; a run is one record per trace it touches.
 // ---------------------------------------------------------------------------------------------
@@ -136,11 +143,11 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
     __shared__ int wq[kMaxWh + 1];       // per wave: private-page quota, then its start position
     __shared__ int wcnt[kMaxWh + 1];     // per wave: record count, then record offset
     __shared__ int scratch[32];
-    __shared__ int S_s, minnb_s;
+    __shared__ int S_s, minfull_s;
     const int tid = threadIdx.x;
     const int N = a.N, Wh = a.Wh;
 
-    if (tid == 0) { S_s = kMaxShared; minnb_s = 0x7fffffff; }
+    if (tid == 0) { S_s = kMaxShared; minfull_s = 0x7fffffff; }
     __syncthreads();
     // lengths, live ranks
     for (int t = tid; t < 2 * kPlanThreads; t += kPlanThreads) {
@@ -152,24 +159,28 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
             a.cnt2[t] = 0;
             a.first2[t] = 0;
         }
-        // shortest live trace: one LDS atomic per wave
-        int mn = nb > 0 ? nb : 0x7fffffff;
+        // fewest full pages of a live trace (the shared prefix is whole pages that every live trace
+        // attends to completely): one LDS atomic per wave
+        int mn = nb > 0 ? L / kPageTokens : 0x7fffffff;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) mn = min(mn, __shfl_xor(mn, off));
-        if ((tid & 63) == 0 && mn != 0x7fffffff) atomicMin(&minnb_s, mn);
+        if ((tid & 63) == 0 && mn != 0x7fffffff) atomicMin(&minfull_s, mn);
         if (t < kMaxPlanN) { nb_s[t] = nb; len_s[t] = L; P_s[t] = nb > 0 ? 1 : 0; }
     }
     __syncthreads();
     const int n_live = array_excl_scan(P_s, N, scratch);   // P_s[t] = rank of trace t
     for (int t = tid; t < N; t += kPlanThreads) {
         a.rank[t] = P_s[t];
-        if (nb_s[t] > 0) live_list[P_s[t]] = t;
+        if (nb_s[t] > 0) {
+            live_list[P_s[t]] = t;
+            a.live[P_s[t]] = t;
+        }
     }
     __syncthreads();
     // shared prefix: compare every live row with the first live row
     int S = 0;
     if (n_live >= 2) {
-        const int cap = min(kMaxShared, minnb_s);
+        const int cap = min(kMaxShared, minfull_s);
         if (tid == 0) S_s = cap;
         __syncthreads();
         const int32_t *row0 = a.block_tables + (size_t)live_list[0] * a.MAXB;
@@ -200,11 +211,24 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         S = S_s;
     }
     int parts = 0, sc = 0;
-    if (S > 0) {
+    const bool mfma = a.prefix_qt > 0 && S > 0;
+    if (mfma) {
+        // attn_prefix runs one wave per (KV head, block of 16 * qt query rows, sub-chunk): enough
+        // sub-chunks for about one wave per SIMD, whole page pairs per sub-chunk
+        const int G = a.Hq / a.Hkv;
+        const int nqb = (n_live * G + 16 * a.prefix_qt - 1) / (16 * a.prefix_qt);
+        parts = max(1, min(min(kMaxParts, (S + 1) / 2), (Wh + nqb - 1) / nqb));
+        parts = min(parts, 1 + 4 * Wh / n_live);  // n_live * parts <= 4 Wh + n_live records (workspace bound)
+        sc = (S + parts - 1) / parts;
+        sc += sc & 1;
+        parts = (S + sc - 1) / sc;
+    } else if (S > 0) {
         parts = max(1, min(min(kMaxParts, S), Wh / n_live));
         sc = (S + parts - 1) / parts;
         parts = (S + sc - 1) / sc;
     }
+    if (mfma)
+        for (int j = tid; j < S; j += kPlanThreads) a.shared_pages[j] = a.block_tables[(size_t)live_list[0] * a.MAXB + j];
     const int N1 = n_live * parts;  // shared-prefix records
     // private pages: prefix over traces
     __syncthreads();
@@ -212,13 +236,14 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
     __syncthreads();
     const int T2 = array_excl_scan(P_s, N, scratch);
     if (tid == 0) P_s[N] = T2;
-    const long long T_all = (long long)T2 + (long long)n_live * S;
+    const long long T_all = (long long)T2 + (mfma ? 0 : (long long)n_live * S);
     const int Q = (int)((T_all + Wh - 1) / Wh);
     // per wave: pages of its shared-prefix records, private quota
     auto part_pages = [&](int p) { return min(sc, S - p * sc); };
     for (int wh = tid; wh < Wh; wh += kPlanThreads) {
         int a_wh = 0;
-        for (int s = wh; s < N1; s += Wh) a_wh += part_pages(s / n_live);
+        if (!mfma)
+            for (int s = wh; s < N1; s += Wh) a_wh += part_pages(s / n_live);
         wq[wh] = max(Q - a_wh, 0);
     }
     __syncthreads();
@@ -291,6 +316,8 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         a.hdr->parts = parts;
         a.hdr->shared = S;
         a.hdr->quota = Q;
+        a.hdr->part_pages = sc;
+        a.hdr->prefix_mfma = mfma ? 1 : 0;
         a.hdr->stamp = a.stamp;
     }
 }
@@ -302,7 +329,9 @@ __device__ __forceinline__ bool plan_usable(const AttnArgs &a)
 {
     const PlanHeader *h = a.hdr;
     const bool ok = h->stamp == a.stamp && h->n1 >= 0 && h->total >= h->n1 && h->total <= a.max_records &&
-                    h->n_live >= 0 && h->n_live <= a.N && h->parts >= 0 && h->parts <= kMaxParts;
+                    h->n_live >= 0 && h->n_live <= a.N && h->parts >= 0 && h->parts <= kMaxParts &&
+                    h->n1 == h->n_live * h->parts && h->shared >= 0 && h->shared <= a.MAXB && h->part_pages >= 0 &&
+                    (long long)h->parts * h->part_pages >= h->shared;
     if (!ok && threadIdx.x == 0) report(a.status, STEP_EPLAN);
     return ok;
 }
@@ -323,6 +352,7 @@ __global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
     const int g = blockIdx.x % a.Hkv;
     const int rec_id = blockIdx.x / a.Hkv;
     if (!plan_usable(a) || rec_id >= a.hdr->total) return;
+    if (a.hdr->prefix_mfma && rec_id < a.hdr->n1) return;  // attn_prefix writes these partials
     const Record rec = a.records[rec_id];
     const int i = rec.i, n = rec.n;
     if ((u32)i >= (u32)a.N || rec.first < 0 || n < 1 || (long long)rec.first + n > a.MAXB || rec.ntok < 1 ||
@@ -458,6 +488,230 @@ __global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
     }
 }
 
+// max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
+__device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
+
+// ---------------------------------------------------------------------------------------------
+// shared prefix on the matrix cores.  The S leading pages are the same physical pages for every live
+// trace, so for one KV head the n_live * G query rows that attend to them form a dense matrix: the
+// logits are K Q^T and the output V^T P^T, both v_mfma_f32_16x16x32_bf16, and every shared tile is
+// read once per block of query rows instead of once per trace.  One wave per (KV head, block of
+// 16 * QT query rows, sub-chunk p of the prefix); it writes the partial (m, l, acc) of the shared-prefix
+// records p * n_live + rank, exactly what stage 1 would have written for them, so the merge does
+// not change.
+//
+// Operand layouts (lane = 16 * gr + c; a lane holds 8 contraction slots, and slot e of lane group gr
+// of A meets slot e of lane group gr of B):
+//   logits  S^T = K Q^T   A = K tile: row = token c, slots = d in [32 kb + 8 gr, +8)   (16-byte load)
+//                         B = Q:      column = query row c, the same d                  (16-byte load)
+//                         result: lane holds tokens 4 gr + j (j < 4) of query column c
+//   output  O^T = V^T P^T B = P^T:    column = query c; slots 0..3 = the lane's own 4 weights of the
+//                                     pair's first page, 4..7 = of its second page (no data movement)
+//                         A = V^T:    tile j, row c <-> d = DB c + j; slots as for P^T.  The lane
+//                                     loads, for its 8 tokens, the DB consecutive values d in
+//                                     [DB c, DB c + DB) (16 bytes at D = 128) and transposes the
+//                                     8 x DB block in registers with v_perm_b32.
+//                         result: tile j, lane holds d = DB (4 gr + jj) + j: over the DB tiles, the 2 DB
+//                                 consecutive values d in [4 DB gr, 4 DB gr + 4 DB) of query column c
+// ---------------------------------------------------------------------------------------------
+template <int D, int QT>
+__device__ __forceinline__ void prefix_unit(const AttnArgs &a, int unit)
+{
+    constexpr int KB = D / 32;  // contraction blocks of the logits
+    constexpr int DB = D / 16;  // output tiles
+    constexpr int VW = DB / 2;  // dwords of one V row a lane holds
+    typedef u32 VRow __attribute__((ext_vector_type(VW)));
+    const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
+    if (!plan_usable(a)) return;
+    const PlanHeader *hd = a.hdr;
+    if (!hd->prefix_mfma) return;
+    const int S = hd->shared, parts = hd->parts, n_live = hd->n_live, sc = hd->part_pages;
+    const int G = a.Hq / a.Hkv;
+    const int rows = n_live * G;
+    const int nqb = (a.N * G + 16 * QT - 1) / (16 * QT);
+    int u = unit;
+    const int g = u % a.Hkv;
+    u /= a.Hkv;
+    const int qb = u % nqb, p = u / nqb;
+    if (p >= parts || qb * 16 * QT >= rows) return;
+    const int first = p * sc, n = min(sc, S - first);
+    if (n < 1 || S > kMaxShared || a.NP <= 0) {
+        if (lane == 0) report(a.status, a.NP <= 0 ? STEP_EPAGE : STEP_EPLAN);
+        return;
+    }
+
+    bool bad_plan = false, bad_page = false;
+    auto trace_of_rank = [&](int rk) {
+        const int t = a.live[rk];
+        const bool ok = (u32)t < (u32)a.N;
+        bad_plan |= !ok;
+        return ok ? t : 0;
+    };
+    const int32_t *bt = a.shared_pages + first;  // first + n <= S <= kMaxShared
+    auto page_at = [&](int j) {
+        const int pg = bt[min(j, n - 1)];
+        const bool ok = (u32)pg < (u32)a.NP;
+        bad_page |= !ok;
+        return ok ? pg : 0;
+    };
+
+    // query rows of this block: row = rank * G + head-in-group
+    uint4 qf[QT][KB];
+    int rank_of[QT], hh_of[QT];
+    bool valid[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int row = (qb * QT + qt) * 16 + c;
+        valid[qt] = row < rows;
+        const int rw = valid[qt] ? row : 0;
+        rank_of[qt] = rw / G;
+        hh_of[qt] = rw % G;
+        const uint16_t *qrow = a.q + ((size_t)trace_of_rank(rank_of[qt]) * a.Hq + g * G + hh_of[qt]) * D;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(qrow + kb * 32 + gr * 8);
+            qf[qt][kb] = valid[qt] ? x : make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    const size_t tile = (size_t)kPageTokens * D;  // bf16 elements per (page, head) tile
+    auto load_pair = [&](int j, uint4 (&kf)[2][KB], VRow (&vr)[8]) {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+            const size_t base = ((size_t)page_at(j + pg) * a.Hkv + g) * tile;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+                kf[pg][kb] = *reinterpret_cast<const uint4 *>(a.k_pages + base + c * D + kb * 32 + gr * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                vr[pg * 4 + e] = *reinterpret_cast<const VRow *>(a.v_pages + base + (4 * gr + e) * D + DB * c);
+        }
+    };
+
+    f32x4 o[QT][DB];
+    float m[QT], l[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        m[qt] = kMinusBig;
+        l[qt] = 0.f;
+#pragma unroll
+        for (int j = 0; j < DB; ++j) o[qt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // one page pair: logits, online softmax, weights straight into the second product
+    auto attend_pair = [&](const uint4 (&kf)[2][KB], const VRow (&vr)[8], bool second) {
+        // V^T operands of the pair
+        uint4 vf[DB];
+#pragma unroll
+        for (int jt = 0; jt < DB; ++jt) {
+            const u32 sel = (jt & 1) ? 0x07060302u : 0x05040100u;
+            u32 w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w[k] = __builtin_amdgcn_perm(vr[2 * k + 1][jt / 2], vr[2 * k][jt / 2], sel);
+            vf[jt] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[0][kb]),
+                                                             __builtin_bit_cast(bf16x8, qf[qt][kb]), s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[1][kb]),
+                                                             __builtin_bit_cast(bf16x8, qf[qt][kb]), s1, 0, 0, 0);
+            }
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[e] = s0[e] * a.scale_log2;
+                x[4 + e] = second ? s1[e] * a.scale_log2 : -INFINITY;
+            }
+            float mx = x[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) mx = max_nc(mx, x[e]);
+            mx = max_nc(mx, __shfl_xor(mx, 16));
+            mx = max_nc(mx, __shfl_xor(mx, 32));
+            const float m_new = max_nc(m[qt], mx);
+            const float alpha = __builtin_amdgcn_exp2f(m[qt] - m_new);
+            m[qt] = m_new;
+            u32 pw[4];
+            float lsum = 0.f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bf16x2 pk = {(__bf16)__builtin_amdgcn_exp2f(x[2 * k] - m_new),
+                                   (__bf16)__builtin_amdgcn_exp2f(x[2 * k + 1] - m_new)};
+                pw[k] = __builtin_bit_cast(u32, pk);
+                lsum += bf16_lo(pw[k]) + bf16_hi(pw[k]);  // the weights as V sees them
+            }
+            l[qt] = fmaf(l[qt], alpha, lsum);
+            const bf16x8 pt = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+            // after the first pairs the running maximum rarely moves: rescale only when some column's did
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int jt = 0; jt < DB; ++jt) o[qt][jt] *= alpha;
+            }
+#pragma unroll
+            for (int jt = 0; jt < DB; ++jt)
+                o[qt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[jt]), pt, o[qt][jt], 0, 0, 0);
+        }
+    };
+
+    // NBUF pair buffers in rotation: the loads of the next NBUF - 1 pairs are in flight while a pair is
+    // used (a sub-chunk is a handful of pairs, so most of its tiles are requested at once)
+    constexpr int NBUF = QT == 1 ? 3 : 2;
+    uint4 kf[NBUF][2][KB];
+    VRow vr[NBUF][8];
+    // the units that share this sub-chunk (same KV head, other query blocks) walk its pairs in
+    // rotated orders, so that they do not all ask the L2 for the same lines at the same moment
+    const int np = (n + 1) / 2;
+    const int rot = qb % np;
+    auto pair_at = [&](int t) { return 2 * ((t + rot) % np); };  // first page of the t-th pair visited
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b)
+        if (b < np) load_pair(pair_at(b), kf[b], vr[b]);
+    for (int t0 = 0; t0 < np; t0 += NBUF) {
+#pragma unroll
+        for (int b = 0; b < NBUF; ++b) {
+            const int t = t0 + b;
+            if (t < np) {
+                // an odd sub-chunk ends on half a pair: that pair's second page gets no weight
+                attend_pair(kf[b], vr[b], pair_at(t) + 1 < n);
+                if (t + NBUF < np) load_pair(pair_at(t + NBUF), kf[b], vr[b]);
+            }
+        }
+    }
+
+    // partial of record p * n_live + rank, head hh: lane (gr, c) holds d in [4 DB gr, 4 DB gr + 4 DB)
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        float ls = l[qt];
+        ls += __shfl_xor(ls, 16);
+        ls += __shfl_xor(ls, 32);
+        if (!valid[qt]) continue;
+        const size_t slot = ((size_t)p * n_live + rank_of[qt]) * a.Hkv + g;
+        float *pacc = a.part_acc + slot * ((size_t)G * D) + (size_t)hh_of[qt] * D + 4 * DB * gr;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int j4 = 0; j4 < DB; j4 += 4)
+                *reinterpret_cast<float4 *>(pacc + DB * jj + j4) =
+                    make_float4(o[qt][j4][jj], o[qt][j4 + 1][jj], o[qt][j4 + 2][jj], o[qt][j4 + 3][jj]);
+        if (gr == 0) {
+            float *pml = a.part_ml + slot * ((size_t)G * 2) + hh_of[qt] * 2;
+            pml[0] = m[qt];
+            pml[1] = ls;
+        }
+    }
+    if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
+    if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
+}
+
+template <int D, int QT>
+__global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
+{
+    prefix_unit<D, QT>(a, (int)blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------------------------
 // stage 1, G == 4 (the Qwen3-8B-like shape and the tiny config): persistent, software-pipelined.
 //   phase A(page) : logits of the page (bf16 dot2), transposing reduction that leaves each lane
@@ -494,11 +748,9 @@ __device__ __forceinline__ void bfly_stage(float (&val)[NV], int c)
     }
 }
 
-// max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
-__device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
 
 template <int D>
-__global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
+__device__ __forceinline__ void stream_g4(const AttnArgs &a, int wave_id)
 {
     constexpr int G = 4;
     constexpr int LPR = D / 8, TPI = 64 / LPR, IPP = kPageTokens / TPI, NV = IPP * G;
@@ -512,8 +764,8 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     // consecutive XCDs, so with Hkv == 8 every XCD streams (and caches) the tiles of one KV head.
     // Its records: the shared-prefix records wh, wh + Wh, ... below n1, then the private-page
     // records n1 + [off2[wh], off2[wh + 1]).
-    const int g = blockIdx.x % a.Hkv;
-    const int wh = blockIdx.x / a.Hkv;
+    const int g = wave_id % a.Hkv;
+    const int wh = wave_id / a.Hkv;
     if (!plan_usable(a)) return;
     const int n1 = a.hdr->n1;
     const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
@@ -531,7 +783,8 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         }
         return nx < p2_end ? nx : -1;
     };
-    int rec_id = wh < n1 ? wh : (p2_begin < p2_end ? p2_begin : -1);
+    // (with attn_prefix the shared-prefix records are not this kernel's)
+    int rec_id = (wh < n1 && !a.hdr->prefix_mfma) ? wh : (p2_begin < p2_end ? p2_begin : -1);
     if (rec_id < 0) return;
     if (a.NP <= 0) {
         if (lane == 0) report(a.status, STEP_EPAGE);
@@ -796,6 +1049,15 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 
+// The prefix units are a launch of their own ahead of this one: run inside this launch, next to the
+// streaming waves, they were measured to cost more than they do alone (every streaming wave has the
+// same share of pages, so the wave that shares its SIMD longest sets the kernel's end).
+template <int D>
+__global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
+{
+    stream_g4<D>(a, (int)blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------------------------
 // stage 2: out[i][h][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c, rounded to bf16
 // ---------------------------------------------------------------------------------------------
@@ -922,8 +1184,19 @@ int waves_per_head(const step_attn_dims *d)
     return wh;
 }
 
+// The shared prefix goes to the matrix cores (attn_prefix) unless the environment variable
+// STEP_ATTN_PREFIX is "0" (read once; testing aid: stage 1 then streams the prefix per trace).
+bool prefix_enabled()
+{
+    static const bool on = [] {
+        const char *s = getenv("STEP_ATTN_PREFIX");
+        return !(s && s[0] == '0');
+    }();
+    return on;
+}
+
 struct Layout {  // byte offsets into the workspace, all multiples of 256
-    size_t off2, records, rank, first2, cnt2, ml, acc, total;
+    size_t off2, records, rank, first2, cnt2, live, shared_pages, ml, acc, total;
     int Wh, max_records;
 };
 
@@ -933,14 +1206,17 @@ Layout layout_for(const step_attn_dims *d)
 {
     Layout l;
     l.Wh = waves_per_head(d);
-    l.max_records = 2 * l.Wh + 2 * d->N;
+    // private pages: at most Wh + N records; shared prefix: at most 4 Wh + N (attn_prefix), Wh + N otherwise
+    l.max_records = 6 * l.Wh + 2 * d->N;
     const size_t R = (size_t)l.max_records, G = d->Hq / d->Hkv, N = d->N;
     l.off2 = 256;
     l.records = l.off2 + up256((size_t)(l.Wh + 1) * sizeof(int32_t));
     l.rank = l.records + up256(R * sizeof(Record));
     l.first2 = l.rank + up256(N * sizeof(int32_t));
     l.cnt2 = l.first2 + up256(N * sizeof(int32_t));
-    l.ml = l.cnt2 + up256(N * sizeof(int32_t));
+    l.live = l.cnt2 + up256(N * sizeof(int32_t));
+    l.shared_pages = l.live + up256(N * sizeof(int32_t));
+    l.ml = l.shared_pages + up256(kMaxShared * sizeof(int32_t));
     l.acc = l.ml + up256(R * d->Hkv * G * 2 * sizeof(float));
     l.total = l.acc + up256(R * d->Hkv * G * d->D * sizeof(float));
     return l;
@@ -958,6 +1234,12 @@ template <int D, int G>
 int launch(const AttnArgs &a, hipStream_t s, int what)
 {
     if (what & kDoPlan) hipLaunchKernelGGL(attn_plan, dim3(1), dim3(kPlanThreads), 0, s, a);
+    const int prefix_units = a.prefix_qt ? a.Hkv * ((a.N * G + 16 * a.prefix_qt - 1) / (16 * a.prefix_qt)) * kMaxParts : 0;
+    if ((what & kDoAttend) && prefix_units) {
+        const dim3 grid((u32)prefix_units);
+        if (a.prefix_qt == 2) hipLaunchKernelGGL((attn_prefix<D, 2>), grid, dim3(64), 0, s, a);
+        else hipLaunchKernelGGL((attn_prefix<D, 1>), grid, dim3(64), 0, s, a);
+    }
     if (what & kDoAttend) {
         // when profiling, the stage-1 launch carries its own start/stop events: they take the
         // kernel's begin and end timestamps, with no marker processing inside the interval
@@ -1003,14 +1285,18 @@ int run(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages, con
     a.rank = reinterpret_cast<int32_t *>(ws + l.rank);
     a.first2 = reinterpret_cast<int32_t *>(ws + l.first2);
     a.cnt2 = reinterpret_cast<int32_t *>(ws + l.cnt2);
+    a.live = reinterpret_cast<int32_t *>(ws + l.live);
+    a.shared_pages = reinterpret_cast<int32_t *>(ws + l.shared_pages);
     a.part_ml = reinterpret_cast<float *>(ws + l.ml);
     a.part_acc = reinterpret_cast<float *>(ws + l.acc);
     a.out = out; a.status = status;
     a.N = d->N; a.Hq = d->Hq; a.Hkv = d->Hkv; a.MAXB = d->MAXB; a.NP = d->NP;
     a.Wh = l.Wh; a.max_records = l.max_records;
+    // query tiles per prefix wave: 2 once there are enough query rows to fill the chip that way
+    a.prefix_qt = !prefix_enabled() ? 0 : ((long long)d->N * (d->Hq / d->Hkv) >= 256) ? 2 : 1;
     // never 0, so a cleared workspace never passes for a plan
     a.stamp = (int)((0x5157u ^ ((u32)d->N * 2654435761u) ^ ((u32)d->MAXB * 40503u) ^ ((u32)d->NP * 2246822519u) ^
-                     ((u32)d->Hkv << 24) ^ ((u32)l.Wh << 12)) | 1u);
+                     ((u32)d->Hkv << 24) ^ ((u32)l.Wh << 12) ^ ((u32)a.prefix_qt << 8)) | 1u);
     a.scale_log2 = d->scale * 1.4426950408889634f;
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

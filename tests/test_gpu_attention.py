@@ -88,7 +88,7 @@ def test_scaled_down_config3_fragmented_pool():
     check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
 
 
-def test_page_permutation_and_private_prefix_copies_are_bit_identical():
+def test_page_permutation_is_bit_identical_and_private_prefix_copies_agree():
     lens = [700, 1300, 64 + 5]
     lay, q, k, v = build(8, lens, 8, 2, 128, prompt=64, slack=1.0, poison=False)
     a = run_gpu(q, k, v, lay.block_tables, lay.seq_lens)
@@ -105,7 +105,42 @@ def test_page_permutation_and_private_prefix_copies_are_bit_identical():
         for j in range(4):
             k3[nxt] = k[lay.block_tables[i, j]]; v3[nxt] = v[lay.block_tables[i, j]]
             bt3[i, j] = nxt; nxt += 1
-    assert np.array_equal(a, run_gpu(q, k3, v3, bt3, lay.seq_lens))
+    # a shared prefix is computed on the matrix cores, private copies by the streaming kernel: the
+    # same mathematical result through two summation orders
+    b, want = check(q, k3, v3, bt3, lay.seq_lens)
+    assert np.all(np.abs(a - b) <= 2.0 ** -7 * np.abs(want) + 4e-3)
+    assert np.abs(a - want).max() <= TOL
+
+
+def test_shared_prefix_streamed_per_trace_when_the_matrix_core_path_is_off():
+    """STEP_ATTN_PREFIX=0 (read once per process, hence the child process) keeps the shared prefix in
+    the streaming kernel; both ways of computing it meet the same bar."""
+    import json, os, subprocess, sys
+    code = (
+        "import sys, json; sys.path.insert(0, %r)\n"
+        "import numpy as np, torch, oracle\n"
+        "from paper_2601_09093_amd import binding, workloads as wl\n"
+        "from tests.gpu_util import dev, dev_bits, host_f32_of_bf16, new_status\n"
+        "errs = []\n"
+        "for D, Hq, Hkv, prompt in ((128, 8, 2, 272), (64, 4, 1, 64), (128, 16, 2, 1024)):\n"
+        "    lens = prompt + wl.rng_for(61, D).integers(1, 900, 20)\n"
+        "    lay = wl.build_layout(lens, prompt, 16, wl.rng_for(61, 1), slack=1.2)\n"
+        "    q = wl.normal_bf16(wl.rng_for(61, 2), (20, Hq, D))\n"
+        "    k = wl.normal_bf16(wl.rng_for(61, 3), (lay.NP, Hkv, 16, D)); v = wl.normal_bf16(wl.rng_for(61, 4), k.shape)\n"
+        "    wl.poison_unused(k, v, lay, 16)\n"
+        "    st = new_status()\n"
+        "    out = binding.paged_decode_attn(dev_bits(q), dev_bits(k), dev_bits(v), dev(lay.block_tables), dev(lay.seq_lens), status=st)\n"
+        "    torch.cuda.synchronize()\n"
+        "    want = oracle.paged_decode_attn(q, k, v, lay.block_tables, lay.seq_lens)\n"
+        "    errs.append([int(st.item()), float(np.abs(host_f32_of_bf16(out) - want).max())])\n"
+        "print(json.dumps(errs))\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ)
+    env["STEP_ATTN_PREFIX"] = "0"
+    res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stderr[-2000:]
+    for status, err in json.loads(res.stdout.strip().splitlines()[-1]):
+        assert status == 0 and err <= TOL
 
 
 def test_large_logits_and_dominant_key():
