@@ -177,7 +177,11 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         }
     }
     __syncthreads();
-    // shared prefix: compare every live row with the first live row
+    // shared prefix: compare every live row with the first live row.  The first live row's leading
+    // entries are also what attn_prefix walks: fetched here, next to the compare loads, stored below
+    const bool copies_row0 = a.prefix_qt > 0 && n_live >= 2 && tid < min(kMaxShared, a.MAXB);
+    int row0_entry = -1;
+    if (copies_row0) row0_entry = a.block_tables[(size_t)live_list[0] * a.MAXB + tid];
     int S = 0;
     if (n_live >= 2) {
         const int cap = min(kMaxShared, minfull_s);
@@ -227,8 +231,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         sc = (S + parts - 1) / parts;
         parts = (S + sc - 1) / sc;
     }
-    if (mfma)
-        for (int j = tid; j < S; j += kPlanThreads) a.shared_pages[j] = a.block_tables[(size_t)live_list[0] * a.MAXB + j];
+    if (copies_row0) a.shared_pages[tid] = row0_entry;  // entries [0, S) are the shared pages
     const int N1 = n_live * parts;  // shared-prefix records
     // private pages: prefix over traces
     __syncthreads();
@@ -549,7 +552,7 @@ __device__ __forceinline__ void prefix_unit(const AttnArgs &a, int unit)
     };
     const int32_t *bt = a.shared_pages + first;  // first + n <= S <= kMaxShared
     auto page_at = [&](int j) {
-        const int pg = bt[min(j, n - 1)];
+        const int pg = __builtin_amdgcn_readfirstlane(bt[min(j, n - 1)]);  // the same for every lane: keep it scalar
         const bool ok = (u32)pg < (u32)a.NP;
         bad_page |= !ok;
         return ok ? pg : 0;
@@ -574,17 +577,21 @@ __device__ __forceinline__ void prefix_unit(const AttnArgs &a, int unit)
         }
     }
 
-    const size_t tile = (size_t)kPageTokens * D;  // bf16 elements per (page, head) tile
+    // a tile's address is a wave-uniform base (page id from a scalar load) plus a 32-bit lane offset
+    // plus a constant: one scalar multiply per page, no per-lane 64-bit arithmetic
+    const size_t tile_bytes = (size_t)kPageTokens * D * 2;
+    const u32 k_lane = (u32)(c * D + gr * 8) * 2;
+    const u32 v_lane = (u32)(4 * gr * D + DB * c) * 2;
     auto load_pair = [&](int j, uint4 (&kf)[2][KB], VRow (&vr)[8]) {
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg) {
-            const size_t base = ((size_t)page_at(j + pg) * a.Hkv + g) * tile;
+            const size_t base = ((size_t)page_at(j + pg) * a.Hkv + g) * tile_bytes;
+            const char *kt = reinterpret_cast<const char *>(a.k_pages) + base;
+            const char *vt = reinterpret_cast<const char *>(a.v_pages) + base;
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-                kf[pg][kb] = *reinterpret_cast<const uint4 *>(a.k_pages + base + c * D + kb * 32 + gr * 8);
+            for (int kb = 0; kb < KB; ++kb) kf[pg][kb] = *reinterpret_cast<const uint4 *>(kt + k_lane + kb * 64);
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                vr[pg * 4 + e] = *reinterpret_cast<const VRow *>(a.v_pages + base + (4 * gr + e) * D + DB * c);
+            for (int e = 0; e < 4; ++e) vr[pg * 4 + e] = *reinterpret_cast<const VRow *>(vt + v_lane + e * D * 2);
         }
     };
 
