@@ -3,14 +3,15 @@
 
 A "step" is one pass of the whole path over N parallel traces of one prompt:
     paged_decode_attn  ->  step_score (+ running-mean update)  ->  prune_free
-on synthetic inputs shaped like the paper's N = 64 workload (benchmark configs[2]: 32 query /
+on synthetic inputs shaped like the paper's N = 64 workload (workload config 3: 32 query /
 8 KV heads, head_dim 128, 16-token pages, a shared 1024-token prompt and tails of 8k-32k tokens in
 a fragmented page pool; scorer 4096 -> 1024 -> 1 on 4 boundary hidden states; Algorithm 1's prune
 of the single lowest-scoring trace).  Inputs are resident in HBM before the timed region.
 Every step gets its own copy of the (small) mutable state so that pruning does not shrink the
 next step's work.
 
-Prints ONE JSON line (see README for the fields).  The dominant kernel's roofline is
+Prints ONE JSON line: metric, value, unit, ms_per_step, config, plus "roofline" (the dominant
+kernel against the HBM peak) and "cpu_baseline" (the oracle on the host cores).  The roofline is
 measured live with HIP events around the stage-1 attention kernel of every timed step.
 """
 import argparse
@@ -31,7 +32,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5], help="BASELINE.json config (1-based)")
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5], help="workload config, 1-based (3: the N = 64 headline)")
     ap.add_argument("--layers", type=int, default=None, help="layers per step (default: the config's; config 4: 36)")
     ap.add_argument("--prune-k", type=int, default=None, help="traces pruned per step (default 1; config 5: 64)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
@@ -63,7 +64,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not "
-              "supported. DESIGN.md describes how the path would shard." % args.gpus, file=sys.stderr)
+              "supported." % args.gpus, file=sys.stderr)
         sys.exit(2)
     if int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: WORLD_SIZE > 1 is not supported (one GPU only)", file=sys.stderr)
@@ -234,6 +235,8 @@ def main():
                  + (int(nb.sum()) - (shared_pages * n_live if prefix_mfma else 0)) * 4   # block-table entries
                  + s.N * s.Hq * s.D * 2                             # q
                  + items * G * (s.D + 2) * 4)                       # split-K partials written by stage 1
+    # the "requested" variant counts every trace's own view of its context (the shared prompt N times)
+    req_bytes = alg_bytes + (lay.requested_tokens - lay.unique_tokens) * s.kv_bytes_per_token
     avg_ms = float(np.mean(stage1_ms))
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
     workload = "config%d" % args.config + ("-loop" if args.mode == "loop" else "")
@@ -241,7 +244,7 @@ def main():
         "kernel": "attn_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": traffic_from_profiles("attn_partial", "config%d" % args.config),
-        "algorithmic_bytes": int(alg_bytes), "avg_kernel_ms": round(avg_ms, 4),
+        "algorithmic_bytes": int(alg_bytes), "requested_bytes": int(req_bytes), "avg_kernel_ms": round(avg_ms, 4),
         "min_kernel_ms": round(float(np.min(stage1_ms)), 4), "launches": len(stage1_ms),
     }
 

@@ -517,8 +517,12 @@ __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amd
 //                         result: tile j, lane holds d = DB (4 gr + jj) + j: over the DB tiles, the 2 DB
 //                                 consecutive values d in [4 DB gr, 4 DB gr + 4 DB) of query column c
 // ---------------------------------------------------------------------------------------------
+// These units are a launch of their own, ahead of stage 1.  Run inside the stage-1 launch, next to
+// the streaming waves (both fit on a SIMD), they were measured to cost more than they do alone: every
+// streaming wave owns the same share of pages, so the wave that shares its SIMD longest sets the
+// kernel's end.
 template <int D, int QT>
-__device__ __forceinline__ void prefix_unit(const AttnArgs &a, int unit)
+__global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
 {
     constexpr int KB = D / 32;  // contraction blocks of the logits
     constexpr int DB = D / 16;  // output tiles
@@ -532,7 +536,7 @@ __device__ __forceinline__ void prefix_unit(const AttnArgs &a, int unit)
     const int G = a.Hq / a.Hkv;
     const int rows = n_live * G;
     const int nqb = (a.N * G + 16 * QT - 1) / (16 * QT);
-    int u = unit;
+    int u = blockIdx.x;
     const int g = u % a.Hkv;
     u /= a.Hkv;
     const int qb = u % nqb, p = u / nqb;
@@ -713,12 +717,6 @@ __device__ __forceinline__ void prefix_unit(const AttnArgs &a, int unit)
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 
-template <int D, int QT>
-__global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
-{
-    prefix_unit<D, QT>(a, (int)blockIdx.x);
-}
-
 // ---------------------------------------------------------------------------------------------
 // stage 1, G == 4 (the Qwen3-8B-like shape and the tiny config): persistent, software-pipelined.
 //   phase A(page) : logits of the page (bf16 dot2), transposing reduction that leaves each lane
@@ -755,9 +753,8 @@ __device__ __forceinline__ void bfly_stage(float (&val)[NV], int c)
     }
 }
 
-
 template <int D>
-__device__ __forceinline__ void stream_g4(const AttnArgs &a, int wave_id)
+__global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
 {
     constexpr int G = 4;
     constexpr int LPR = D / 8, TPI = 64 / LPR, IPP = kPageTokens / TPI, NV = IPP * G;
@@ -771,8 +768,8 @@ __device__ __forceinline__ void stream_g4(const AttnArgs &a, int wave_id)
     // consecutive XCDs, so with Hkv == 8 every XCD streams (and caches) the tiles of one KV head.
     // Its records: the shared-prefix records wh, wh + Wh, ... below n1, then the private-page
     // records n1 + [off2[wh], off2[wh + 1]).
-    const int g = wave_id % a.Hkv;
-    const int wh = wave_id / a.Hkv;
+    const int g = blockIdx.x % a.Hkv;
+    const int wh = blockIdx.x / a.Hkv;
     if (!plan_usable(a)) return;
     const int n1 = a.hdr->n1;
     const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
@@ -1054,15 +1051,6 @@ __device__ __forceinline__ void stream_g4(const AttnArgs &a, int wave_id)
     }
     if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
-}
-
-// The prefix units are a launch of their own ahead of this one: run inside this launch, next to the
-// streaming waves, they were measured to cost more than they do alone (every streaming wave has the
-// same share of pages, so the wave that shares its SIMD longest sets the kernel's end).
-template <int D>
-__global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
-{
-    stream_g4<D>(a, (int)blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
