@@ -245,6 +245,7 @@ def main():
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": traffic_from_profiles("attn_partial", "config%d" % args.config),
         "algorithmic_bytes": int(alg_bytes), "requested_bytes": int(req_bytes), "avg_kernel_ms": round(avg_ms, 4),
+        "median_kernel_ms": round(float(np.median(stage1_ms)), 4),
         "min_kernel_ms": round(float(np.min(stage1_ms)), 4), "launches": len(stage1_ms),
     }
 
