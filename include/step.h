@@ -92,7 +92,7 @@ int32_t step_attn_waves_per_head(const step_attn_dims *dims);
  * G == 4, and on pages shared by all live traces, the softmax weights are rounded to bf16 before
  * they multiply V (the normaliser is summed from the same rounded weights).  Result within 2e-2
  * max-abs of the float64 definition for N(0,1) inputs.
- * Leading pages that every live trace has in its block-table row (a shared prompt, up to 256 whole
+ * Leading pages that every live trace has in its block-table row (a shared prompt, up to 1024 whole
  * pages) are found on the device and computed once for all traces on the matrix cores; the
  * environment variable STEP_ATTN_PREFIX=0, read once, turns that off (testing aid: they are then
  * streamed per trace like private pages).  A workspace that holds no plan for these dims makes

@@ -41,7 +41,7 @@ struct Record {       // 16 bytes, read with one scalar load
 constexpr int kMaxParts = 8;     // a shared prefix is cut into at most this many sub-chunks per trace
 constexpr int kMaxPlanN = 2048;  // traces the planner handles
 constexpr int kMaxWh = 2048;     // waves per KV head the planner handles
-constexpr int kMaxShared = 256;  // pages of common prefix looked for (4096 tokens)
+constexpr int kMaxShared = 1024; // pages of common prefix looked for (16384 tokens); <= kPlanThreads
 
 struct PlanHeader {   // 256 bytes
     int32_t total;    // records: [0, n1) cover the shared prefix, [n1, total) the private pages
@@ -91,6 +91,7 @@ struct AttnArgs {
 //      runs whose lengths top every wave up to Q pages; a run is one record per trace it touches.
 // ---------------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
+static_assert(kMaxShared <= kPlanThreads, "one thread copies one entry of the first live row");
 
 // exclusive scan of one int per thread over the workgroup (wave shuffles + 16 wave totals)
 __device__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
@@ -188,30 +189,39 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         if (tid == 0) S_s = cap;
         __syncthreads();
         const int32_t *row0 = a.block_tables + (size_t)live_list[0] * a.MAXB;
-        int first_diff = cap;  // smallest page index at which some live row differs from the first live row
-        // consecutive lanes compare consecutive entries of one row (coalesced); the planner runs
-        // right after gigabytes were streamed through every cache, so all of a thread's loads are
-        // issued before the first compare (16 pairs in flight per thread)
-        constexpr int kBatch = 16;
-        const int work = (n_live - 1) * cap;
-        for (int base = 0; base < work; base += kBatch * kPlanThreads) {
-            int x[kBatch], y[kBatch], jj[kBatch];
+        // the columns are searched kSearchCols at a time and the search stops at the first block that
+        // holds a difference: a prompt of a few dozen pages costs one block however long the traces are
+        constexpr int kSearchCols = 256;
+        for (int c0 = 0; c0 < cap; c0 += kSearchCols) {
+            const int w = min(kSearchCols, cap - c0);
+            int first_diff = cap;  // smallest page index at which some live row differs from the first live row
+            // consecutive lanes compare consecutive entries of one row (coalesced); the planner runs
+            // right after gigabytes were streamed through every cache, so all of a thread's loads are
+            // issued before the first compare (16 pairs in flight per thread)
+            constexpr int kBatch = 16;
+            const int work = (n_live - 1) * w;
+            for (int base = 0; base < work; base += kBatch * kPlanThreads) {
+                int x[kBatch], y[kBatch], jj[kBatch];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int idx = min(base + u * kPlanThreads + tid, work - 1);
-                const int rk = 1 + idx / cap;
-                jj[u] = idx % cap;
-                x[u] = a.block_tables[(size_t)live_list[rk] * a.MAXB + jj[u]];
-                y[u] = row0[jj[u]];
+                for (int u = 0; u < kBatch; ++u) {
+                    const int idx = min(base + u * kPlanThreads + tid, work - 1);
+                    const int rk = 1 + idx / w;
+                    jj[u] = c0 + idx % w;
+                    x[u] = a.block_tables[(size_t)live_list[rk] * a.MAXB + jj[u]];
+                    y[u] = row0[jj[u]];
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                    if (x[u] != y[u]) first_diff = min(first_diff, jj[u]);
             }
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u)
-                if (x[u] != y[u]) first_diff = min(first_diff, jj[u]);
+            for (int off = 32; off >= 1; off >>= 1) first_diff = min(first_diff, __shfl_xor(first_diff, off));
+            if ((tid & 63) == 0 && first_diff < cap) atomicMin(&S_s, first_diff);
+            __syncthreads();
+            // a later block can only lower S_s to a column at or beyond its own start, so every thread
+            // takes the same decision here whenever it reads S_s
+            if (S_s < c0 + w) break;
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) first_diff = min(first_diff, __shfl_xor(first_diff, off));
-        if ((tid & 63) == 0 && first_diff < cap) atomicMin(&S_s, first_diff);
-        __syncthreads();
         S = S_s;
     }
     int parts = 0, sc = 0;

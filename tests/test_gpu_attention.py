@@ -199,7 +199,7 @@ def _shared_layout(seed, lens, shared_pages, P=16, extra_pool=7):
 
 
 @pytest.mark.parametrize("case", ["many_short", "more_traces_than_waves", "single_trace", "all_shared",
-                                  "long_prefix", "prefix_ends_ragged", "two_traces"])
+                                  "long_prefix", "prefix_beyond_search_cap", "prefix_ends_ragged", "two_traces"])
 def test_planner_corner_cases(case):
     """Shapes that push the work planner: shared-prefix detection, sub-chunking, runs that span many
     traces, more live traces than waves per KV head, traces that lie entirely inside the prefix."""
@@ -217,8 +217,11 @@ def test_planner_corner_cases(case):
     elif case == "all_shared":
         lay = wl.build_layout(np.array([160, 160, 160]), 160, P, wl.rng_for(904, 0))   # nothing private
     elif case == "long_prefix":
-        lens = 300 * 16 + r.integers(1, 900, 5)              # 300 shared pages, above the 256-page search cap
+        lens = 300 * 16 + r.integers(1, 900, 5)              # 300 shared pages: two column blocks of the search
         lay = wl.build_layout(lens, 300 * 16, P, wl.rng_for(905, 0))
+    elif case == "prefix_beyond_search_cap":
+        lens = 1100 * 16 + r.integers(1, 500, 3)             # 1100 shared pages, above the 1024-page cap
+        lay = wl.build_layout(lens, 1100 * 16, P, wl.rng_for(909, 0))
     elif case == "prefix_ends_ragged":
         lens = np.array([64 + 9, 64 + 9, 64 + 700])
         lay = wl.build_layout(lens, 64, P, wl.rng_for(906, 0))
