@@ -169,6 +169,12 @@ def test_device_reported_errors():
     run_gpu(q, k, v, lay.block_tables, sl, expect_status=17)      # STEP_ELEN
     sl[0] = -5
     run_gpu(q, k, v, lay.block_tables, sl, expect_status=17)
+    # a page id out of range inside the shared prefix (same bad id in every row) is reported as well
+    lay2, q2, k2, v2 = build(13, [64 + 40, 64 + 300, 64 + 7], 4, 1, 64, prompt=64, poison=False)
+    bt2 = lay2.block_tables.copy(); bt2[:, 1] = lay2.NP + 3
+    run_gpu(q2, k2, v2, bt2, lay2.seq_lens, expect_status=16)
+    bt2[:, 1] = -1
+    run_gpu(q2, k2, v2, bt2, lay2.seq_lens, expect_status=16)
     # garbage in unused block-table entries is ignored
     bt = lay.block_tables.copy(); bt[0, 7:] = 123456789
     got = run_gpu(q, k, v, bt, lay.seq_lens)
