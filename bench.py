@@ -43,6 +43,7 @@ def parse_args():
                          "pruning) + KV append + attention + scorer")
     ap.add_argument("--free-pages", type=int, default=16,
                     help="loop mode: free pages left in the pool at the start (the rest is marked occupied)")
+    ap.add_argument("--graph", action="store_true", help="record the K timed steps as one HIP graph and time its replay")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="only run libstep's plain copy kernel on MIB MiB (profiler byte-counter calibration)")
     return ap.parse_args()
@@ -203,10 +204,22 @@ def main():
     # state copies: W warm-up steps, K timed steps, K more steps with stage 1 bracketed by events
     for i in range(W):
         step(i)
+    graph = None
+    if args.graph:
+        # the K timed steps recorded once as a HIP graph (every entry point only enqueues kernels);
+        # the timed region replays it
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(W, W + K):
+                step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(W, W + K):
-        step(i)
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(W, W + K):
+            step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     # the same K steps again with HIP events around the stage-1 attention kernel of every step (the
@@ -260,7 +273,7 @@ def main():
                        sc.hidden.shape[1], sc.W1.shape[0], "ReLU" if sc.act == 0 else "GELU", B),
                    "prune_k": prune_k, "attn_waves_per_kv_head": binding.attn_waves_per_head(adims),
                    "attn_records": records, "shared_prefix_pages_on_mfma": shared_pages if prefix_mfma else 0,
-                   "mode": args.mode},
+                   "mode": args.mode, "launch": "hip-graph" if args.graph else "stream"},
         "attn_hbm_gbs": round(achieved, 1), "attn_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "roofline": roofline,
     }
