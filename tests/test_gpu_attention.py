@@ -192,6 +192,16 @@ def test_host_reported_errors():
     with pytest.raises(binding.StepError) as e:
         binding.paged_decode_attn(bad, kb, kb, tb, tl, workspace=torch.zeros(1 << 20, dtype=torch.uint8, device=DEV))
     assert e.value.code == 1
+    for shape_q, shape_k in (((2049, 4, 64), (2, 1, 16, 64)),      # more traces than the planner handles
+                             ((1, 6, 64), (2, 2, 16, 64)),         # group size 3
+                             ((1, 5, 64), (2, 2, 16, 64))):        # Hq not a multiple of Hkv
+        bq = torch.zeros(shape_q, dtype=torch.int16, device=DEV)
+        bk = torch.zeros(shape_k, dtype=torch.int16, device=DEV)
+        with pytest.raises(binding.StepError) as e:
+            binding.paged_decode_attn(bq, bk, bk, torch.zeros((shape_q[0], 2), dtype=torch.int32, device=DEV),
+                                      torch.ones(shape_q[0], dtype=torch.int32, device=DEV),
+                                      workspace=torch.zeros(1 << 20, dtype=torch.uint8, device=DEV))
+        assert e.value.code == 1
     # N = 0 is a valid no-op
     binding.paged_decode_attn(tq[:0], tk, tv, tb[:0], tl[:0])
     torch.cuda.synchronize()
@@ -205,7 +215,8 @@ def _shared_layout(seed, lens, shared_pages, P=16, extra_pool=7):
 
 
 @pytest.mark.parametrize("case", ["many_short", "more_traces_than_waves", "single_trace", "all_shared",
-                                  "long_prefix", "prefix_beyond_search_cap", "prefix_ends_ragged", "two_traces"])
+                                  "long_prefix", "prefix_beyond_search_cap", "prefix_ends_ragged",
+                                  "most_traces_the_planner_takes", "two_traces"])
 def test_planner_corner_cases(case):
     """Shapes that push the work planner: shared-prefix detection, sub-chunking, runs that span many
     traces, more live traces than waves per KV head, traces that lie entirely inside the prefix."""
@@ -232,6 +243,10 @@ def test_planner_corner_cases(case):
         lens = np.array([64 + 9, 64 + 9, 64 + 700])
         lay = wl.build_layout(lens, 64, P, wl.rng_for(906, 0))
         lay.block_tables[1, 4] = lay.block_tables[0, 4]      # traces 0 and 1 also share their ragged last page
+    elif case == "most_traces_the_planner_takes":
+        lens = 64 + r.integers(1, 120, 2048); lens[5::97] = 0   # N = 2048, four shared pages
+        lay = wl.build_layout(lens, 64, P, wl.rng_for(910, 0), slack=1.0)
+        Hq, Hkv = 4, 1                                           # one KV head: 1024 waves on it
     else:
         lens = np.array([4000, 17])
         lay = wl.build_layout(lens, 16, P, wl.rng_for(907, 0))
