@@ -524,7 +524,7 @@ __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amd
 //                                     loads, for its 8 tokens, the DB consecutive values d in
 //                                     [DB c, DB c + DB) (16 bytes at D = 128) and transposes the
 //                                     8 x DB block in registers with v_perm_b32.
-//                         result: tile j, lane holds d = DB (4 gr + jj) + j: over the DB tiles, the 2 DB
+//                         result: tile j, lane holds d = DB (4 gr + jj) + j: over the DB tiles, the 4 DB
 //                                 consecutive values d in [4 DB gr, 4 DB gr + 4 DB) of query column c
 // ---------------------------------------------------------------------------------------------
 // These units are a launch of their own, ahead of stage 1.  Run inside the stage-1 launch, next to
