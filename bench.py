@@ -188,12 +188,11 @@ def main():
         n_pruned_l = torch.zeros(1, dtype=torch.int32, device=dev)
         new_pages_l = torch.empty(s.N, dtype=torch.int32, device=dev)
         ws_res = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(s.N, lay.MAXB, lay.NP)), dev)
-        pruned_total = torch.zeros(1, dtype=torch.int32, device=dev)
+        live_at_start = int((lay.seq_lens > 0).sum())
 
         def step(i):  # noqa: F811  (replaces the per-copy step above)
             binding.reserve_pages(scores, rc_l, bt_l, sl_l, pruned=pruned_l, n_pruned=n_pruned_l,
                                   new_pages=new_pages_l, workspace=ws_res, status=status)
-            pruned_total.add_(n_pruned_l)
             binding.append_kv(k_new, v_new, k_pages, v_pages, bt_l, sl_l, refcounts=rc_l, status=status)
             binding.paged_decode_attn(q, k_pages, v_pages, bt_l, sl_l, out=out, workspace=ws_attn, status=status)
             binding.step_score(hidden, bidx, W1, b1, W2, b2, act=sc.act, logits=logits, probs=probs,
@@ -279,7 +278,8 @@ def main():
     }
 
     if args.mode == "loop":
-        result["config"]["traces_pruned_by_memory_trigger"] = int(pruned_total.item())
+        # nothing else ends a trace in this loop, so the difference is what the memory trigger pruned
+        result["config"]["traces_pruned_by_memory_trigger"] = live_at_start - int((sl_l > 0).sum().item())
         result["config"]["live_traces_at_end"] = int((sl_l > 0).sum().item())
         result["config"]["free_pages_at_start"] = args.free_pages
     if not args.no_cpu_baseline and args.mode == "step":
