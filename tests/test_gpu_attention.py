@@ -287,6 +287,42 @@ def test_random_shapes_and_length_mixes(seed):
     assert np.all(got[lay.seq_lens == 0] == 0)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_trace_counts_and_prefix_lengths(seed):
+    """A second seeded sweep, wider in the number of traces (1 to 600) and in the shared prefix (0 to 300
+    pages, around the 256-column blocks of the planner's search), with traces that end exactly at the
+    prefix, many dead traces and short tails."""
+    r = wl.rng_for(90000 + seed, 0)
+    D = int(r.choice([64, 128, 128]))
+    G = int(r.choice([1, 2, 4, 4, 4, 8]))
+    Hkv = int(r.choice([1, 2, 3, 4, 5, 8, 10]))
+    N = int(r.choice([1, 2, 3, 7, 16, 33, 64, 100, 257, 600]))
+    prompt_pages = int(r.choice([0, 0, 1, 2, 3, 5, 17, 64, 255, 256, 257, 300]))
+    if N >= 257:
+        prompt_pages = min(prompt_pages, 17)
+    prompt = prompt_pages * P
+    maxtail = int(r.choice([20, 200, 1500, 4000])) if N <= 64 else int(r.choice([20, 200]))
+    lens = r.integers(0 if prompt else 1, maxtail + 1, N) + prompt
+    if prompt and r.random() < 0.5:
+        lens[r.integers(0, N)] = prompt                           # a trace with nothing private
+    lens[r.random(N) < r.choice([0.0, 0.1, 0.5])] = 0
+    if not np.any(lens > 0):
+        lens[0] = max(prompt, 1)
+    nb_max = max(int((lens.max() + P - 1) // P), 1)
+    lay = wl.build_layout(lens, prompt, P, wl.rng_for(90000 + seed, 1), slack=float(r.choice([1.0, 1.5])),
+                          maxb=nb_max + int(r.integers(0, 5)))
+    q = wl.normal_bf16(wl.rng_for(90000 + seed, 2), (N, G * Hkv, D), float(r.choice([0.5, 1.0, 3.0])))
+    k = wl.normal_bf16(wl.rng_for(90000 + seed, 3), (lay.NP, Hkv, P, D))
+    v = wl.normal_bf16(wl.rng_for(90000 + seed, 4), (lay.NP, Hkv, P, D))
+    wl.poison_unused(k, v, lay, P)
+    got = run_gpu(q, k, v, lay.block_tables, lay.seq_lens)
+    want = oracle.paged_decode_attn(q, k, v, lay.block_tables, lay.seq_lens)
+    err = np.abs(got - want)
+    # short traces of large values: the bf16 rounding of the output alone is 2^-9 |out|
+    assert np.all(np.isfinite(got)) and np.all(err <= 2.0 ** -8 * np.abs(want) + 6e-3), float(err.max())
+    assert err.max() <= TOL and np.all(got[lay.seq_lens == 0] == 0)
+
+
 def test_full_config2():
     w = wl.make_workload(2)
     check(w.q, w.k_pages, w.v_pages, w.layout.block_tables, w.layout.seq_lens)
