@@ -130,13 +130,14 @@ def test_weighted_vote_bit_exact():
     assert int(w.item()) == -1
 
 
-def test_multi_step_decode_loop_on_device():
-    """150 decode steps of 8 traces that share a 2-page prompt, in a pool too small for all of them:
+def _decode_loop(NP):
+    """150 decode steps of 8 traces that share a 2-page prompt in a pool of NP pages:
     reserve (memory-triggered pruning + allocation) -> append -> attention -> scorer -> running mean,
     every step on the device; the oracle replays the same steps (fed the GPU's step probabilities,
-    so that the scores are the same bytes) and every integer state must match bit for bit."""
+    so that the scores are the same bytes) and every integer state must match bit for bit.
+    Returns (traces pruned by the memory trigger, traces alive at the end)."""
     N, Hq, Hkv, D, d, m = 8, 4, 1, 64, 256, 64
-    steps, NP, MAXB = 150, 44, 16
+    steps, MAXB = 150, 16
     r = wl.rng_for(77, 0)
     lay = wl.build_layout(np.full(N, 32), 32, P, wl.rng_for(77, 1), slack=1.0, maxb=MAXB)
     rc = np.concatenate([lay.refcounts, np.zeros(NP - lay.NP, np.int32)])
@@ -185,8 +186,24 @@ def test_multi_step_decode_loop_on_device():
         if bidx.size:
             assert np.abs(logits.cpu().numpy() - o_logits).max() <= 1e-3, step
     assert np.array_equal(host_bits(t_k), k) and np.array_equal(host_bits(t_v), v)
-    assert total_pruned >= 3 and (sl > 0).sum() >= 1          # the pool forced pruning, and no step failed to allocate
+    assert (sl > 0).sum() >= 1 and np.all(sl[sl > 0] == 32 + steps)   # no step failed to allocate: survivors never waited
     # the survivors vote
     answers = np.where(sl > 0, np.arange(N) % 3, -1).astype(np.int32)
     w, wt = binding.weighted_vote(dev(answers), t_scores)
-    assert (int(w.item()), np.float32(wt.item())) == tuple(map(lambda x: x, (oracle.weighted_vote(answers, scores)[0], np.float32(oracle.weighted_vote(answers, scores)[1]))))
+    o_w, o_wt = oracle.weighted_vote(answers, scores)
+    assert int(w.item()) == o_w and np.float32(wt.item()) == np.float32(o_wt)
+    return total_pruned, int((sl > 0).sum())
+
+
+def test_multi_step_decode_loop_on_device():
+    pruned, alive = _decode_loop(44)                          # a pool too small for all eight traces
+    assert pruned >= 3 and alive == 8 - pruned
+
+
+def test_memory_budget_sweep_prunes_fewer_traces_with_more_memory():
+    """The shape of the paper's memory-budget sweep (Table 4) on synthetic traces: the same 150-step
+    run in pools of growing size prunes fewer and fewer traces and none once everything fits
+    (8 traces x 10 private pages + 2 prompt pages = 82 pages at the end); in every pool each
+    surviving trace got its page at every boundary."""
+    counts = [_decode_loop(NP)[0] for NP in (30, 60, 90)]
+    assert counts[0] >= counts[1] >= counts[2] == 0 and counts[0] > counts[1]
