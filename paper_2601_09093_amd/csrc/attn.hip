@@ -299,10 +299,11 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan(const AttnArgs a)
         a.records[rec] = r;
     };
     for (int wh = tid; wh < Wh; wh += kPlanThreads) {
-        for (int s = wh; s < N1; s += Wh) {
-            const int p = s / n_live;
-            emit(s, live_list[s % n_live], p * sc, part_pages(p));
-        }
+        if (!mfma)  // attn_prefix takes its sub-chunks from the header and the live list, not from records
+            for (int s = wh; s < N1; s += Wh) {
+                const int p = s / n_live;
+                emit(s, live_list[s % n_live], p * sc, part_pages(p));
+            }
         int rec = N1 + wcnt[wh];
         int pos = wq[wh];
         const int end = min(wq[wh + 1], T2);
