@@ -179,7 +179,9 @@ def main():
         rc_np = lay.refcounts.copy()
         free_ids = np.nonzero(rc_np == 0)[0]
         rc_np[free_ids[args.free_pages:]] = 1                       # occupied by someone else
-        rc_l, bt_l, sl_l = t(rc_np), t(lay.block_tables), t(lay.seq_lens)
+        # the rows get a few spare entries: a trace that sits at the config's length cap still grows
+        bt_np = np.pad(lay.block_tables, ((0, 0), (0, (2 * K + W) // s.P + 2)), constant_values=-1)
+        rc_l, bt_l, sl_l = t(rc_np), t(bt_np), t(lay.seq_lens)
         sum_l, cnt_l = t(sum0), t(cnt0)
         scores.copy_(t((sum0 / cnt0).astype(np.float32)))
         k_new = torch.randn((s.N, s.Hkv, s.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
@@ -187,7 +189,7 @@ def main():
         pruned_l = torch.empty(s.N, dtype=torch.int32, device=dev)
         n_pruned_l = torch.zeros(1, dtype=torch.int32, device=dev)
         new_pages_l = torch.empty(s.N, dtype=torch.int32, device=dev)
-        ws_res = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(s.N, lay.MAXB, lay.NP)), dev)
+        ws_res = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(s.N, bt_np.shape[1], lay.NP)), dev)
         live_at_start = int((lay.seq_lens > 0).sum())
 
         def step(i):  # noqa: F811  (replaces the per-copy step above)
