@@ -78,3 +78,31 @@ def test_scaled_down_config5_whole_step():
         assert sorted(g["pruned"].tolist()) == sorted(o_ind["pruned"].tolist())
         assert np.array_equal(g["freed"], o_ind["freed"]) and np.array_equal(g["rc"], o_ind["rc"])
     assert np.all(g["rc"][w.layout.block_tables[0, :64]] == 32 - k)
+
+
+def test_every_call_accepts_a_null_status_pointer():
+    """status may be NULL: errors are dropped, results are the same, and a data-dependent error (a page id
+    out of range) still touches nothing outside the arrays."""
+    w = wl.make_workload(1, poison=True)
+    lay, s = w.layout, w.scorer
+    want = gpu_step(w, 1)
+    bt, sl, rc = dev(lay.block_tables), dev(lay.seq_lens), dev(lay.refcounts)
+    out = binding.paged_decode_attn(dev_bits(w.q), dev_bits(w.k_pages), dev_bits(w.v_pages), bt, sl)
+    ssum, cnt = dev(s.score_sum), dev(s.score_cnt)
+    scores = torch.empty(w.shape.N, dtype=torch.float32, device=DEV)
+    logits, _ = binding.step_score(dev_bits(s.hidden), dev(s.boundary_idx), dev_bits(s.W1), dev(s.b1), dev_bits(s.W2),
+                                   torch.tensor([s.b2], dtype=torch.float32, device=DEV), act=s.act,
+                                   trace_of=dev(s.trace_of), score_sum=ssum, score_cnt=cnt, scores=scores)
+    pruned, freed, nf = binding.prune_free(scores, 1, rc, bt, sl)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_f32_of_bf16(out), want["out"]) and np.array_equal(logits.cpu().numpy(), want["logits"])
+    assert pruned.cpu().numpy()[:1].tolist() == want["pruned"].tolist() and np.array_equal(rc.cpu().numpy(), want["rc"])
+    # errors without a status word
+    bad = lay.block_tables.copy(); bad[:, 0] = lay.NP + 7; bad[2, 5] = -3
+    tb, tl, trc = dev(bad), dev(lay.seq_lens), dev(lay.refcounts)
+    out = binding.paged_decode_attn(dev_bits(w.q), dev_bits(w.k_pages), dev_bits(w.v_pages), tb, tl)
+    binding.prune_free(dev(np.array([0.3, 0.1, 0.2, 0.4], np.float32)), 2, trc, tb, tl)
+    binding.reserve_pages(dev(np.array([0.3, 0.1, 0.2, 0.4], np.float32)), trc, tb, tl)
+    binding.append_kv(dev_bits(w.q[:, :1]), dev_bits(w.q[:, :1]), dev_bits(w.k_pages.copy()), dev_bits(w.v_pages.copy()), tb, tl)
+    torch.cuda.synchronize()
+    assert out.shape == (w.shape.N, w.shape.Hq, w.shape.D)
