@@ -88,9 +88,9 @@ int32_t step_attn_waves_per_head(const step_attn_dims *dims);
  *   seq_lens     [N]               int32
  *   out          [N][Hq][D]        bf16, written for every trace
  *   workspace    >= step_attn_workspace_bytes(dims), 256-byte aligned; holds split-K partials
- * Arithmetic: exact bf16 products, fp32 accumulation, fp32 running max and exponentials; for
- * G == 4, and on pages shared by all live traces, the softmax weights are rounded to bf16 before
- * they multiply V (the normaliser is summed from the same rounded weights).  Result within 2e-2
+ * Arithmetic: exact bf16 products, fp32 accumulation, fp32 running max and exponentials; the
+ * softmax weights are rounded to bf16 before they multiply V (the normaliser is summed from the
+ * same rounded weights).  Result within 2e-2
  * max-abs of the float64 definition for N(0,1) inputs.
  * Leading pages that every live trace has in its block-table row (a shared prompt, up to 1024 whole
  * pages) are found on the device and computed once for all traces on the matrix cores; the

@@ -10,16 +10,17 @@
 //   attn_prefix  the shared pages on the matrix cores: for one KV head the query rows of all live
 //                traces form a dense matrix, so logits and output are two MFMA products and every
 //                shared tile is read once per block of query rows instead of once per trace.
-//   attn_partial stage 1, the HBM-streaming kernel over the private pages.  One 64-lane wavefront per
-//                (record, KV head).  A (page, head) tile is P*D bf16 contiguous; the wave reads it
-//                with 16-byte loads, lane l taking bytes [j*1024 + 16 l, +16) on load j, so every
-//                load instruction covers 1 KB of consecutive addresses.  A row of D values lives in
-//                LPR = D/8 neighbouring lanes and each group of LPR lanes ("row group" r) sees the
-//                tokens r, r+TPI, ... of every page: TPI = 64/LPR independent online-softmax streams
-//                per wave, merged once per record.  The G query heads share every K and V register.
-//                For G == 4 the kernel is persistent: each wave walks its own list of records and
-//                starts the next record's first tile loads before it reduces and stores the current
-//                record's partial, so no load latency is exposed between records.
+//   stage 1      the HBM-streaming kernels over the private pages: persistent single-wave workgroups,
+//                one per resident wave slot, each walking its own list of records with the loads of the
+//                next pages (and of the next record) in flight.
+//                attn_partial_g4 (G == 4): a (page, head) tile is P*D bf16 contiguous; the wave reads
+//                it with 16-byte loads, lane l taking bytes [j*1024 + 16 l, +16) on load j.  A row of D
+//                values lives in LPR = D/8 neighbouring lanes and each group of LPR lanes ("row group"
+//                r) sees the tokens r, r+TPI, ... of every page: TPI = 64/LPR independent online-softmax
+//                streams per wave, merged once per record; the 4 query heads share every K and V
+//                register (bf16 dot2 on the vector ALUs).
+//                attn_partial_mfma (G in {1, 2, 8}): the two products on the matrix cores with the G
+//                query heads of the trace in the columns, so the arithmetic per byte does not grow with G.
 //   attn_merge   stage 2: per (trace, query head) combine the record partials (m, l, acc), round to
 //                bf16.
 #include <hip/hip_ext.h>
@@ -350,158 +351,6 @@ __device__ __forceinline__ bool plan_usable(const AttnArgs &a)
     return ok;
 }
 
-// ---------------------------------------------------------------------------------------------
-// stage 1, any group size: one wave per (record, kv head), plain all-reduce of the logits
-// ---------------------------------------------------------------------------------------------
-template <int D, int G>
-__global__ __launch_bounds__(64) void attn_partial(const AttnArgs a)
-{
-    constexpr int LPR = D / 8;              // lanes per token row
-    constexpr int TPI = 64 / LPR;           // token rows per load instruction
-    constexpr int IPP = kPageTokens / TPI;  // load instructions per (page, head) tile
-    constexpr int NV = IPP * G;             // logits per lane per page
-
-    const int lane = threadIdx.x;
-    const int r = lane / LPR, c = lane % LPR;
-    const int g = blockIdx.x % a.Hkv;
-    const int rec_id = blockIdx.x / a.Hkv;
-    if (!plan_usable(a) || rec_id >= a.hdr->total) return;
-    if (a.hdr->prefix_mfma && rec_id < a.hdr->n1) return;  // attn_prefix writes these partials
-    const Record rec = a.records[rec_id];
-    const int i = rec.i, n = rec.n;
-    if ((u32)i >= (u32)a.N || rec.first < 0 || n < 1 || (long long)rec.first + n > a.MAXB || rec.ntok < 1 ||
-        rec.ntok > kPageTokens) {
-        if (lane == 0) report(a.status, STEP_EPLAN);
-        return;
-    }
-
-    uint4 qv[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-        qv[h] = *reinterpret_cast<const uint4 *>(a.q + ((size_t)i * a.Hq + (size_t)g * G + h) * D + c * 8);
-
-    float m[G], l[G], acc[G][8];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m[h] = kMinusBig;
-        l[h] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
-    }
-
-    const int32_t *bt = a.block_tables + (size_t)i * a.MAXB + rec.first;
-    const size_t tile_elems = (size_t)kPageTokens * D;
-    bool bad_page = false;
-
-    for (int j = 0; j < n; ++j) {
-        const int page = bt[j];
-        if ((u32)page >= (u32)a.NP) {
-            bad_page = true;
-            continue;
-        }
-        const int ntok = j == n - 1 ? rec.ntok : kPageTokens;
-        const size_t off = ((size_t)page * a.Hkv + g) * tile_elems;
-        const uint4 *kt = reinterpret_cast<const uint4 *>(a.k_pages + off);
-        const uint4 *vt = reinterpret_cast<const uint4 *>(a.v_pages + off);
-        uint4 k[IPP], v[IPP];
-#pragma unroll
-        for (int jj = 0; jj < IPP; ++jj) k[jj] = kt[jj * 64 + lane];
-#pragma unroll
-        for (int jj = 0; jj < IPP; ++jj) v[jj] = vt[jj * 64 + lane];
-        if (ntok < kPageTokens) {  // slots >= ntok hold garbage (maybe NaN)
-#pragma unroll
-            for (int jj = 0; jj < IPP; ++jj)
-                if (jj * TPI + r >= ntok) {
-                    k[jj] = make_uint4(0, 0, 0, 0);
-                    v[jj] = make_uint4(0, 0, 0, 0);
-                }
-        }
-        float val[NV];
-#pragma unroll
-        for (int jj = 0; jj < IPP; ++jj)
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float s = dot2_bf16(k[jj].x, qv[h].x, 0.f);
-                s = dot2_bf16(k[jj].y, qv[h].y, s);
-                s = dot2_bf16(k[jj].z, qv[h].z, s);
-                s = dot2_bf16(k[jj].w, qv[h].w, s);
-#pragma unroll
-                for (int off2 = LPR / 2; off2 >= 1; off2 >>= 1) s += __shfl_xor(s, off2);
-                s *= a.scale_log2;
-                if (ntok < kPageTokens && jj * TPI + r >= ntok) s = -INFINITY;
-                val[jj * G + h] = s;
-            }
-        float pv[NV];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            float mx = val[h];
-#pragma unroll
-            for (int jj = 1; jj < IPP; ++jj) mx = fmaxf(mx, val[jj * G + h]);
-            const float m_new = fmaxf(m[h], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m[h] - m_new);
-            m[h] = m_new;
-            l[h] *= alpha;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
-#pragma unroll
-            for (int jj = 0; jj < IPP; ++jj) {
-                const float p = __builtin_amdgcn_exp2f(val[jj * G + h] - m_new);
-                pv[jj * G + h] = p;
-                l[h] += p;
-            }
-        }
-#pragma unroll
-        for (int jj = 0; jj < IPP; ++jj) {
-            const u32 w[4] = {v[jj].x, v[jj].y, v[jj].z, v[jj].w};
-            float vf[8];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                vf[2 * t] = bf16_lo(w[t]);
-                vf[2 * t + 1] = bf16_hi(w[t]);
-            }
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float pw = pv[jj * G + h];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pw, vf[e], acc[h][e]);
-            }
-        }
-    }
-    if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
-
-    // merge the TPI row-group streams of this wave, write the record's partial
-    const size_t slot = (size_t)rec_id * a.Hkv + g;
-    float *pacc = a.part_acc + slot * (G * D);
-    float *pml = a.part_ml + slot * (G * 2);
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        float M = m[h];
-#pragma unroll
-        for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
-        const float f = __builtin_amdgcn_exp2f(m[h] - M);
-        float ls = l[h] * f;
-#pragma unroll
-        for (int off = LPR; off < 64; off <<= 1) ls += __shfl_xor(ls, off);
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float x = acc[h][e] * f;
-#pragma unroll
-            for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
-            o[e] = x;
-        }
-        if (r == 0) {
-            float4 *dst = reinterpret_cast<float4 *>(pacc + h * D + c * 8);
-            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-            dst[1] = make_float4(o[4], o[5], o[6], o[7]);
-            if (c == 0) {
-                pml[h * 2 + 0] = M;
-                pml[h * 2 + 1] = ls;
-            }
-        }
-    }
-}
-
 // max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
 __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
 
@@ -722,6 +571,264 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
             float *pml = a.part_ml + slot * ((size_t)G * 2) + hh_of[qt] * 2;
             pml[0] = m[qt];
             pml[1] = ls;
+        }
+    }
+    if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
+    if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
+}
+
+// ---------------------------------------------------------------------------------------------
+// stage 1 on the matrix cores, any group size: the persistent streaming kernel for G != 4.
+// The same two products as attn_prefix with the G query heads of ONE trace in the columns (the other
+// 16 - G columns are zero and never stored), over the private pages of the wave's records, pair of
+// pages by pair of pages.  The operand loads (K: 16 rows x 64 bytes per instruction, V: 4 rows x
+// 256 bytes) stream a fragmented pool as fast as the 1 KB-per-instruction loads of the G == 4 kernel
+// (measured on a bare read probe: 6.79 against 6.81 TB/s), and the arithmetic per byte no longer grows
+// with G.  Page ids, records and tiles are requested ahead of their use across record boundaries:
+// the wave's page pairs form one sequence, a load cursor runs kBufs pairs ahead of the compute cursor.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
+{
+    constexpr int KB = D / 32, DB = D / 16, VW = DB / 2;
+    constexpr int kBufs = 3;
+    typedef u32 VRow __attribute__((ext_vector_type(VW)));
+    typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
+    const int g = blockIdx.x % a.Hkv;
+    const int wh = blockIdx.x / a.Hkv;
+    if (!plan_usable(a)) return;
+    const int G = a.Hq / a.Hkv;
+    const int n1 = a.hdr->n1;
+    const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
+    if (p2_begin < n1 || p2_end < p2_begin || p2_end > a.hdr->total) {
+        if (lane == 0) report(a.status, STEP_EPLAN);
+        return;
+    }
+    auto next_record = [&](int id) {  // id of the record after `id` in this wave's list, -1 at the end
+        int nx;
+        if (id < n1) {
+            nx = id + a.Wh;
+            if (nx >= n1) nx = p2_begin;
+        } else {
+            nx = id + 1;
+        }
+        return nx < p2_end ? nx : -1;
+    };
+    const int first_id = (wh < n1 && !a.hdr->prefix_mfma) ? wh : (p2_begin < p2_end ? p2_begin : -1);
+    if (first_id < 0) return;
+    if (a.NP <= 0) {
+        if (lane == 0) report(a.status, STEP_EPAGE);
+        return;
+    }
+
+    bool bad_plan = false, bad_page = false;
+    auto record_at = [&](int id) {  // a record that points outside the block tables is replaced and reported
+        Record x = a.records[id];
+        const bool ok = (u32)x.i < (u32)a.N && x.first >= 0 && x.n >= 1 && (long long)x.first + x.n <= a.MAXB &&
+                        x.ntok >= 1 && x.ntok <= kPageTokens;
+        bad_plan |= !ok;
+        if (!ok) x = Record{0, 0, 1, 1};
+        return x;
+    };
+
+    // a position in the wave's sequence of page pairs: pages j and j + 1 of record id
+    struct Cursor {
+        int id;      // < 0: past the end
+        int next_id; // the record after it
+        Record rec, next_rec;
+        int j;
+    };
+    auto enter = [&](int id, const Record &rec) {  // first pair of record id; its successor is fetched now, used later
+        Cursor x;
+        x.id = id;
+        x.rec = rec;
+        x.j = 0;
+        x.next_id = id >= 0 ? next_record(id) : -1;
+        x.next_rec = x.next_id >= 0 ? record_at(x.next_id) : Record{0, 0, 1, 1};
+        return x;
+    };
+    auto advance = [&](Cursor &x) {
+        x.j += 2;
+        if (x.j >= x.rec.n) x = enter(x.next_id, x.next_rec);
+    };
+    auto page_ids = [&](const Cursor &x, int &p0, int &p1) {  // second page of an odd record's last pair: the last page again
+        const int32_t *row = a.block_tables + (size_t)x.rec.i * a.MAXB + x.rec.first;
+        p0 = row[x.j];
+        p1 = row[min(x.j + 1, x.rec.n - 1)];
+    };
+
+    const size_t tile_bytes = (size_t)kPageTokens * D * 2;
+    const u32 k_lane = (u32)(c * D + gr * 8) * 2;
+    const u32 v_lane = (u32)(4 * gr * D + DB * c) * 2;
+    auto tile_of = [&](int page) {
+        const int pg = __builtin_amdgcn_readfirstlane(page);
+        const bool ok = (u32)pg < (u32)a.NP;
+        bad_page |= !ok;
+        return ((size_t)(ok ? pg : 0) * a.Hkv + g) * tile_bytes;
+    };
+    // KV tiles are read once: non-temporal loads (streaming cache policy)
+    auto load_pair = [&](int p0, int p1, uint4 (&kf)[2][KB], VRow (&vr)[8]) {
+        const int pgs[2] = {p0, p1};
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+            const size_t base = tile_of(pgs[pg]);
+            const char *kt = reinterpret_cast<const char *>(a.k_pages) + base;
+            const char *vt = reinterpret_cast<const char *>(a.v_pages) + base;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kt + k_lane + kb * 64));
+                kf[pg][kb] = make_uint4(t.x, t.y, t.z, t.w);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                vr[pg * 4 + e] = __builtin_nontemporal_load(reinterpret_cast<const VRow *>(vt + v_lane + e * D * 2));
+        }
+    };
+    auto load_q = [&](int trace, uint4 (&qf)[KB]) {  // column c = query head g * G + c of the trace, zero beyond G
+        const uint16_t *qrow = a.q + ((size_t)trace * a.Hq + g * G + min(c, G - 1)) * D;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(qrow + kb * 32 + gr * 8);
+            qf[kb] = c < G ? x : make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    // per record: running max, weight sum (this lane group's tokens) and output tiles of column c
+    f32x4 o[DB];
+    float m = kMinusBig, l = 0.f;
+    uint4 qf[KB];
+
+    auto attend_pair = [&](const uint4 (&kf)[2][KB], VRow (&vr)[8], int ntok0, int ntok1) {
+        const bool ragged = ntok0 < kPageTokens || ntok1 < kPageTokens;
+        if (ragged) {  // rows past the trace's last token may hold anything (NaN included)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (4 * gr + e >= ntok0) vr[e] = VRow(0);
+                if (4 * gr + e >= ntok1) vr[4 + e] = VRow(0);
+            }
+        }
+        uint4 vf[DB];
+#pragma unroll
+        for (int jt = 0; jt < DB; ++jt) {
+            const u32 sel = (jt & 1) ? 0x07060302u : 0x05040100u;
+            u32 w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w[k] = __builtin_amdgcn_perm(vr[2 * k + 1][jt / 2], vr[2 * k][jt / 2], sel);
+            vf[jt] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[0][kb]),
+                                                         __builtin_bit_cast(bf16x8, qf[kb]), s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[1][kb]),
+                                                         __builtin_bit_cast(bf16x8, qf[kb]), s1, 0, 0, 0);
+        }
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = s0[e] * a.scale_log2;
+            x[4 + e] = s1[e] * a.scale_log2;
+        }
+        if (ragged) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (4 * gr + e >= ntok0) x[e] = -INFINITY;
+                if (4 * gr + e >= ntok1) x[4 + e] = -INFINITY;
+            }
+        }
+        float mx = x[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = max_nc(mx, x[e]);
+        mx = max_nc(mx, __shfl_xor(mx, 16));
+        mx = max_nc(mx, __shfl_xor(mx, 32));
+        const float m_new = max_nc(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        u32 pw[4];
+        float lsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bf16x2 pk = {(__bf16)__builtin_amdgcn_exp2f(x[2 * k] - m_new),
+                               (__bf16)__builtin_amdgcn_exp2f(x[2 * k + 1] - m_new)};
+            pw[k] = __builtin_bit_cast(u32, pk);
+            lsum += bf16_lo(pw[k]) + bf16_hi(pw[k]);  // the weights as V sees them
+        }
+        l = fmaf(l, alpha, lsum);
+        const bf16x8 pt = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int jt = 0; jt < DB; ++jt) o[jt] *= alpha;
+        }
+#pragma unroll
+        for (int jt = 0; jt < DB; ++jt)
+            o[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[jt]), pt, o[jt], 0, 0, 0);
+    };
+
+    // pair buffers: tiles, the cursor they belong to and, for the first pair of a record, its queries
+    uint4 kf[kBufs][2][KB];
+    VRow vr[kBufs][8];
+    uint4 qslot[kBufs][KB];
+    Cursor at[kBufs];
+
+    Cursor cur = enter(first_id, record_at(first_id));  // load cursor
+    int id0, id1;                                       // page ids of the load cursor's pair
+    page_ids(cur, id0, id1);
+    auto fill = [&](uint4 (&kfb)[2][KB], VRow (&vrb)[8], uint4 (&qb)[KB], Cursor &slot) {
+        slot = cur;
+        if (cur.id < 0) return;
+        load_pair(id0, id1, kfb, vrb);
+        if (cur.j == 0) load_q(cur.rec.i, qb);
+        advance(cur);
+        if (cur.id >= 0) page_ids(cur, id0, id1);  // used one refill later
+    };
+#pragma unroll
+    for (int b = 0; b < kBufs; ++b) fill(kf[b], vr[b], qslot[b], at[b]);
+
+    bool done = false;
+    while (!done) {
+#pragma unroll
+        for (int b = 0; b < kBufs; ++b) {
+            if (done) continue;
+            const Cursor x = at[b];
+            if (x.id < 0) {
+                done = true;
+                continue;
+            }
+            if (x.j == 0) {  // a new record starts
+                m = kMinusBig;
+                l = 0.f;
+#pragma unroll
+                for (int jt = 0; jt < DB; ++jt) o[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) qf[kb] = qslot[b][kb];
+            }
+            const int n = x.rec.n;
+            auto tokens_of = [&](int jj) { return jj < n - 1 ? kPageTokens : (jj == n - 1 ? x.rec.ntok : 0); };
+            attend_pair(kf[b], vr[b], tokens_of(x.j), tokens_of(x.j + 1));
+            const bool last = x.j + 2 >= n;
+            fill(kf[b], vr[b], qslot[b], at[b]);  // the buffer is free: request the pair kBufs ahead
+            if (last) {  // the record's partial: lane (gr, c) holds d in [4 DB gr, 4 DB gr + 4 DB) of head c
+                float ls = l;
+                ls += __shfl_xor(ls, 16);
+                ls += __shfl_xor(ls, 32);
+                if (c < G) {
+                    const size_t slot = (size_t)x.id * a.Hkv + g;
+                    float *pacc = a.part_acc + slot * ((size_t)G * D) + (size_t)c * D + 4 * DB * gr;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                        for (int j4 = 0; j4 < DB; j4 += 4)
+                            *reinterpret_cast<float4 *>(pacc + DB * jj + j4) =
+                                make_float4(o[j4][jj], o[j4 + 1][jj], o[j4 + 2][jj], o[j4 + 3][jj]);
+                    if (gr == 0) {
+                        float *pml = a.part_ml + slot * ((size_t)G * 2) + c * 2;
+                        pml[0] = m;
+                        pml[1] = ls;
+                    }
+                }
+            }
         }
     }
     if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
@@ -1253,14 +1360,24 @@ int launch(const AttnArgs &a, hipStream_t s, int what)
         hipEvent_t e0 = timed ? g_prof.ev[2 * g_prof.used] : nullptr;
         hipEvent_t e1 = timed ? g_prof.ev[2 * g_prof.used + 1] : nullptr;
         if (timed) ++g_prof.used;
+        // G == 4: the dot2 kernel (about 1 % ahead of the matrix-core kernel at that group size);
+        // STEP_ATTN_G4_MFMA=1, read once, sends G == 4 to the matrix-core kernel too (testing aid)
+        static const bool g4_mfma = [] {
+            const char *e = getenv("STEP_ATTN_G4_MFMA");
+            return e && e[0] == '1';
+        }();
+        const dim3 grid((u32)(a.Wh * a.Hkv));
+        bool launched = false;
         if constexpr (G == 4) {
-            const dim3 grid((u32)(a.Wh * a.Hkv));
-            if (timed) hipExtLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, e0, e1, 0, a);
-            else hipLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, a);
-        } else {
-            const dim3 grid((u32)(a.max_records * a.Hkv));
-            if (timed) hipExtLaunchKernelGGL((attn_partial<D, G>), grid, dim3(64), 0, s, e0, e1, 0, a);
-            else hipLaunchKernelGGL((attn_partial<D, G>), grid, dim3(64), 0, s, a);
+            if (!g4_mfma) {
+                if (timed) hipExtLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, e0, e1, 0, a);
+                else hipLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, a);
+                launched = true;
+            }
+        }
+        if (!launched) {
+            if (timed) hipExtLaunchKernelGGL((attn_partial_mfma<D>), grid, dim3(64), 0, s, e0, e1, 0, a);
+            else hipLaunchKernelGGL((attn_partial_mfma<D>), grid, dim3(64), 0, s, a);
         }
         hipLaunchKernelGGL((attn_merge<D, G>), dim3((u32)(a.N * a.Hq)), dim3(64), 0, s, a);
     }

@@ -112,9 +112,12 @@ def test_page_permutation_is_bit_identical_and_private_prefix_copies_agree():
     assert np.abs(a - want).max() <= TOL
 
 
-def test_shared_prefix_streamed_per_trace_when_the_matrix_core_path_is_off():
-    """STEP_ATTN_PREFIX=0 (read once per process, hence the child process) keeps the shared prefix in
-    the streaming kernel; both ways of computing it meet the same bar."""
+@pytest.mark.parametrize("switches", [{"STEP_ATTN_PREFIX": "0"}, {"STEP_ATTN_G4_MFMA": "1"},
+                                      {"STEP_ATTN_PREFIX": "0", "STEP_ATTN_G4_MFMA": "1"}])
+def test_alternative_kernel_routes_meet_the_same_bar(switches):
+    """STEP_ATTN_PREFIX=0 keeps the shared prefix in the streaming kernels, STEP_ATTN_G4_MFMA=1 sends
+    group size 4 to the matrix-core streaming kernel (both read once per process, hence the child
+    process); every route meets the same bar."""
     import json, os, subprocess, sys
     code = (
         "import sys, json; sys.path.insert(0, %r)\n"
@@ -122,7 +125,7 @@ def test_shared_prefix_streamed_per_trace_when_the_matrix_core_path_is_off():
         "from paper_2601_09093_amd import binding, workloads as wl\n"
         "from tests.gpu_util import dev, dev_bits, host_f32_of_bf16, new_status\n"
         "errs = []\n"
-        "for D, Hq, Hkv, prompt in ((128, 8, 2, 272), (64, 4, 1, 64), (128, 16, 2, 1024)):\n"
+        "for D, Hq, Hkv, prompt in ((128, 8, 2, 272), (64, 4, 1, 64), (128, 16, 2, 1024), (128, 2, 2, 48), (64, 8, 4, 0), (128, 32, 8, 16)):\n"
         "    lens = prompt + wl.rng_for(61, D).integers(1, 900, 20)\n"
         "    lay = wl.build_layout(lens, prompt, 16, wl.rng_for(61, 1), slack=1.2)\n"
         "    q = wl.normal_bf16(wl.rng_for(61, 2), (20, Hq, D))\n"
@@ -136,7 +139,7 @@ def test_shared_prefix_streamed_per_trace_when_the_matrix_core_path_is_off():
         "print(json.dumps(errs))\n"
     ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     env = dict(os.environ)
-    env["STEP_ATTN_PREFIX"] = "0"
+    env.update(switches)
     res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
     assert res.returncode == 0, res.stderr[-2000:]
     for status, err in json.loads(res.stdout.strip().splitlines()[-1]):
