@@ -13,13 +13,13 @@
 //   stage 1      the HBM-streaming kernels over the private pages: persistent single-wave workgroups,
 //                one per resident wave slot, each walking its own list of records with the loads of the
 //                next pages (and of the next record) in flight.
-//                attn_partial_g4 (G == 4): a (page, head) tile is P*D bf16 contiguous; the wave reads
+//                attn_partial_g4 (G == 4, D == 128): a (page, head) tile is P*D bf16 contiguous; the wave reads
 //                it with 16-byte loads, lane l taking bytes [j*1024 + 16 l, +16) on load j.  A row of D
 //                values lives in LPR = D/8 neighbouring lanes and each group of LPR lanes ("row group"
 //                r) sees the tokens r, r+TPI, ... of every page: TPI = 64/LPR independent online-softmax
 //                streams per wave, merged once per record; the 4 query heads share every K and V
 //                register (bf16 dot2 on the vector ALUs).
-//                attn_partial_mfma (G in {1, 2, 8}): the two products on the matrix cores with the G
+//                attn_partial_mfma (every other shape): the two products on the matrix cores with the G
 //                query heads of the trace in the columns, so the arithmetic per byte does not grow with G.
 //   attn_merge   stage 2: per (trace, query head) combine the record partials (m, l, acc), round to
 //                bf16.
@@ -836,7 +836,7 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// stage 1, G == 4 (the Qwen3-8B-like shape and the tiny config): persistent, software-pipelined.
+// stage 1, G == 4 and D == 128 (the shape of all three models of the paper): persistent, software-pipelined.
 //   phase A(page) : logits of the page (bf16 dot2), transposing reduction that leaves each lane
 //                   with one (token, head) logit, running max, p = 2^(x - m), rounded to bf16 and
 //                   packed in token pairs, handed to the row group through LDS.
@@ -876,7 +876,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
 {
     constexpr int G = 4;
     constexpr int LPR = D / 8, TPI = 64 / LPR, IPP = kPageTokens / TPI, NV = IPP * G;
-    static_assert(NV == LPR, "one logit per lane after the transposing reduction");
+    static_assert(D == 128 && NV == LPR, "a row is 16 lanes wide: one logit per lane after the transposing reduction");
     constexpr int NPAIR = IPP / 2;  // token pairs per lane per page
     __shared__ u32 pbuf[2][64];
 
@@ -956,7 +956,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
                 s = dot2_bf16(k[j].w, qv[h].w, s);
                 val[j * G + h] = s;
             }
-        if constexpr (LPR == 16) bfly_stage<3, 16, NV>(val, c);
+        bfly_stage<3, 16, NV>(val, c);
         bfly_stage<2, 8, NV>(val, c);
         bfly_stage<1, 4, NV>(val, c);
         bfly_stage<0, 2, NV>(val, c);
@@ -964,21 +964,15 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         float x = val[0] * a.scale_log2;
         x = ((c / G) * TPI + r < ntok) ? x : -INFINITY;
         float mx = x;
-        if constexpr (LPR == 16) {
-            mx = max_nc(mx, dpp<kDppRowRor4>(mx));
-            mx = max_nc(mx, dpp<kDppRowRor8>(mx));
-        } else {
-            mx = max_nc(mx, __shfl_xor(mx, 4));
-        }
+        mx = max_nc(mx, dpp<kDppRowRor4>(mx));
+        mx = max_nc(mx, dpp<kDppRowRor8>(mx));
         const float m_new = max_nc(m_own, mx);
         const float alpha_own = __builtin_amdgcn_exp2f(m_own - m_new);
         m_own = m_new;
         mx_pending = mx;
         const float p = __builtin_amdgcn_exp2f(x - m_new);
         // lane c + 4 of the row group holds the same head's weight for the next token row
-        float p_next;
-        if constexpr (LPR == 16) p_next = dpp<0x12C>(p);  // row_ror:12 = value of lane (c + 4) % 16
-        else p_next = __shfl_xor(p, 4);
+        const float p_next = dpp<0x12C>(p);  // row_ror:12 = value of lane (c + 4) % 16
         const bf16x2 pk = {(__bf16)p, (__bf16)p_next};
         const u32 w = __builtin_bit_cast(u32, pk);
         l_own = fmaf(l_own, alpha_own, bf16_lo(w));
@@ -1122,12 +1116,8 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
 
         // ---- merge the TPI row-group streams of this wave, write the record's partial ----
         float ls = l_own;
-        if constexpr (LPR == 16) {
-            ls += dpp<kDppRowRor4>(ls);
-            ls += dpp<kDppRowRor8>(ls);
-        } else {
-            ls += __shfl_xor(ls, 4);
-        }
+        ls += dpp<kDppRowRor4>(ls);
+        ls += dpp<kDppRowRor8>(ls);
         float lh[G];
         lh[0] = dpp<STEP_DPP_QUAD_BCAST(0)>(ls);
         lh[1] = dpp<STEP_DPP_QUAD_BCAST(1)>(ls);
@@ -1360,15 +1350,16 @@ int launch(const AttnArgs &a, hipStream_t s, int what)
         hipEvent_t e0 = timed ? g_prof.ev[2 * g_prof.used] : nullptr;
         hipEvent_t e1 = timed ? g_prof.ev[2 * g_prof.used + 1] : nullptr;
         if (timed) ++g_prof.used;
-        // G == 4: the dot2 kernel (about 1 % ahead of the matrix-core kernel at that group size);
-        // STEP_ATTN_G4_MFMA=1, read once, sends G == 4 to the matrix-core kernel too (testing aid)
+        // G == 4, D == 128: the dot2 kernel (about 1 % ahead of the matrix-core kernel at that shape; at
+        // D == 64 the matrix-core kernel is the faster one, 6.2 against 5.5 TB/s);
+        // STEP_ATTN_G4_MFMA=1, read once, sends that shape to the matrix-core kernel too (testing aid)
         static const bool g4_mfma = [] {
             const char *e = getenv("STEP_ATTN_G4_MFMA");
             return e && e[0] == '1';
         }();
         const dim3 grid((u32)(a.Wh * a.Hkv));
         bool launched = false;
-        if constexpr (G == 4) {
+        if constexpr (G == 4 && D == 128) {
             if (!g4_mfma) {
                 if (timed) hipExtLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, e0, e1, 0, a);
                 else hipLaunchKernelGGL((attn_partial_g4<D>), grid, dim3(64), 0, s, a);
