@@ -355,14 +355,7 @@ __device__ __forceinline__ bool plan_usable(const AttnArgs &a)
 __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
 
 // ---------------------------------------------------------------------------------------------
-// shared prefix on the matrix cores.  The S leading pages are the same physical pages for every live
-// trace, so for one KV head the n_live * G query rows that attend to them form a dense matrix: the
-// logits are K Q^T and the output V^T P^T, both v_mfma_f32_16x16x32_bf16, and every shared tile is
-// read once per block of query rows instead of once per trace.  One wave per (KV head, block of
-// 16 * QT query rows, sub-chunk p of the prefix); it writes the partial (m, l, acc) of the shared-prefix
-// records p * n_live + rank, exactly what stage 1 would have written for them, so the merge does
-// not change.
-//
+// The matrix-core form of one page pair, shared by attn_prefix and attn_partial_mfma.
 // Operand layouts (lane = 16 * gr + c; a lane holds 8 contraction slots, and slot e of lane group gr
 // of A meets slot e of lane group gr of B):
 //   logits  S^T = K Q^T   A = K tile: row = token c, slots = d in [32 kb + 8 gr, +8)   (16-byte load)
@@ -377,6 +370,126 @@ __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amd
 //                         result: tile j, lane holds d = DB (4 gr + jj) + j: over the DB tiles, the 4 DB
 //                                 consecutive values d in [4 DB gr, 4 DB gr + 4 DB) of query column c
 // ---------------------------------------------------------------------------------------------
+template <int D>
+struct MfmaPair {
+    static constexpr int KB = D / 32;  // contraction blocks of the logits
+    static constexpr int DB = D / 16;  // output tiles
+    static constexpr int VW = DB / 2;  // dwords of one V row a lane holds
+    typedef u32 VRow __attribute__((ext_vector_type(VW)));
+
+    // V^T operands of a pair from the lane's 8 V rows (rows 0..3: tokens 4 gr + e of the first page,
+    // 4..7: of the second).  ntok0 / ntok1 = tokens of the two pages that belong to the trace: rows
+    // past them may hold anything (NaN included) and are cleared before they meet a zero weight.
+    static __device__ __forceinline__ void v_operands(VRow (&vr)[8], int ntok0, int ntok1, int gr, uint4 (&vf)[DB])
+    {
+        if (ntok0 < kPageTokens || ntok1 < kPageTokens) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (4 * gr + e >= ntok0) vr[e] = VRow(0);
+                if (4 * gr + e >= ntok1) vr[4 + e] = VRow(0);
+            }
+        }
+#pragma unroll
+        for (int jt = 0; jt < DB; ++jt) {
+            const u32 sel = (jt & 1) ? 0x07060302u : 0x05040100u;
+            u32 w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w[k] = __builtin_amdgcn_perm(vr[2 * k + 1][jt / 2], vr[2 * k][jt / 2], sel);
+            vf[jt] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+
+    // logits of one 16-column query tile against the pair, online softmax per column (running max m,
+    // this lane group's share l of the weight sum), weights rounded to bf16 straight into the second
+    // product; the weight sum is taken from the rounded weights, the accumulators are rescaled only
+    // when some column's maximum moved
+    static __device__ __forceinline__ void attend(const uint4 (&kf)[2][KB], const uint4 (&qf)[KB], const uint4 (&vf)[DB],
+                                                  int ntok0, int ntok1, int gr, float scale_log2, float &m, float &l,
+                                                  f32x4 (&o)[DB])
+    {
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[0][kb]),
+                                                         __builtin_bit_cast(bf16x8, qf[kb]), s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[1][kb]),
+                                                         __builtin_bit_cast(bf16x8, qf[kb]), s1, 0, 0, 0);
+        }
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = s0[e] * scale_log2;
+            x[4 + e] = s1[e] * scale_log2;
+        }
+        if (ntok0 < kPageTokens || ntok1 < kPageTokens) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (4 * gr + e >= ntok0) x[e] = -INFINITY;
+                if (4 * gr + e >= ntok1) x[4 + e] = -INFINITY;
+            }
+        }
+        float mx = x[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = max_nc(mx, x[e]);
+        mx = max_nc(mx, __shfl_xor(mx, 16));
+        mx = max_nc(mx, __shfl_xor(mx, 32));
+        const float m_new = max_nc(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        u32 pw[4];
+        float lsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bf16x2 pk = {(__bf16)__builtin_amdgcn_exp2f(x[2 * k] - m_new),
+                               (__bf16)__builtin_amdgcn_exp2f(x[2 * k + 1] - m_new)};
+            pw[k] = __builtin_bit_cast(u32, pk);
+            lsum += bf16_lo(pw[k]) + bf16_hi(pw[k]);  // the weights as V sees them
+        }
+        l = fmaf(l, alpha, lsum);
+        const bf16x8 pt = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int jt = 0; jt < DB; ++jt) o[jt] *= alpha;
+        }
+#pragma unroll
+        for (int jt = 0; jt < DB; ++jt)
+            o[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[jt]), pt, o[jt], 0, 0, 0);
+    }
+
+    // the finished accumulators of query column c as the partial of (slot, head): lane (gr, c) holds d
+    // in [4 DB gr, 4 DB gr + 4 DB); l is this lane group's share of the weight sum
+    static __device__ __forceinline__ void store_partial(const AttnArgs &a, size_t slot, int G, int head, int gr, bool write,
+                                                         float m, float l, const f32x4 (&o)[DB])
+    {
+        float ls = l;
+        ls += __shfl_xor(ls, 16);
+        ls += __shfl_xor(ls, 32);
+        if (!write) return;
+        float *pacc = a.part_acc + slot * ((size_t)G * D) + (size_t)head * D + 4 * DB * gr;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int j4 = 0; j4 < DB; j4 += 4)
+                *reinterpret_cast<float4 *>(pacc + DB * jj + j4) =
+                    make_float4(o[j4][jj], o[j4 + 1][jj], o[j4 + 2][jj], o[j4 + 3][jj]);
+        if (gr == 0) {
+            float *pml = a.part_ml + slot * ((size_t)G * 2) + head * 2;
+            pml[0] = m;
+            pml[1] = ls;
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// shared prefix on the matrix cores.  The S leading pages are the same physical pages for every live
+// trace, so for one KV head the n_live * G query rows that attend to them form a dense matrix: the
+// logits are K Q^T and the output V^T P^T, both v_mfma_f32_16x16x32_bf16, and every shared tile is
+// read once per block of query rows instead of once per trace.  One wave per (KV head, block of
+// 16 * QT query rows, sub-chunk p of the prefix); it writes the partial (m, l, acc) of the shared-prefix
+// records p * n_live + rank, exactly what stage 1 would have written for them, so the merge does
+// not change.
+//
+// (operand layouts: MfmaPair above)
 // These units are a launch of their own, ahead of stage 1.  Run inside the stage-1 launch, next to
 // the streaming waves (both fit on a SIMD), they were measured to cost more than they do alone: every
 // streaming wave owns the same share of pages, so the wave that shares its SIMD longest sets the
@@ -384,10 +497,9 @@ __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amd
 template <int D, int QT>
 __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
 {
-    constexpr int KB = D / 32;  // contraction blocks of the logits
-    constexpr int DB = D / 16;  // output tiles
-    constexpr int VW = DB / 2;  // dwords of one V row a lane holds
-    typedef u32 VRow __attribute__((ext_vector_type(VW)));
+    typedef MfmaPair<D> MP;
+    constexpr int KB = MP::KB, DB = MP::DB;
+    typedef typename MP::VRow VRow;
     const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
     if (!plan_usable(a)) return;
     const PlanHeader *hd = a.hdr;
@@ -469,62 +581,15 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
         for (int j = 0; j < DB; ++j) o[qt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // one page pair: logits, online softmax, weights straight into the second product
-    auto attend_pair = [&](const uint4 (&kf)[2][KB], const VRow (&vr)[8], bool second) {
-        // V^T operands of the pair
+    // one page pair against the QT query tiles; an odd sub-chunk ends on half a pair, whose second page
+    // gets no weight
+    auto attend_pair = [&](const uint4 (&kf)[2][KB], VRow (&vr)[8], bool second) {
+        const int ntok1 = second ? kPageTokens : 0;
         uint4 vf[DB];
+        MP::v_operands(vr, kPageTokens, ntok1, gr, vf);
 #pragma unroll
-        for (int jt = 0; jt < DB; ++jt) {
-            const u32 sel = (jt & 1) ? 0x07060302u : 0x05040100u;
-            u32 w[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) w[k] = __builtin_amdgcn_perm(vr[2 * k + 1][jt / 2], vr[2 * k][jt / 2], sel);
-            vf[jt] = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[0][kb]),
-                                                             __builtin_bit_cast(bf16x8, qf[qt][kb]), s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[1][kb]),
-                                                             __builtin_bit_cast(bf16x8, qf[qt][kb]), s1, 0, 0, 0);
-            }
-            float x[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                x[e] = s0[e] * a.scale_log2;
-                x[4 + e] = second ? s1[e] * a.scale_log2 : -INFINITY;
-            }
-            float mx = x[0];
-#pragma unroll
-            for (int e = 1; e < 8; ++e) mx = max_nc(mx, x[e]);
-            mx = max_nc(mx, __shfl_xor(mx, 16));
-            mx = max_nc(mx, __shfl_xor(mx, 32));
-            const float m_new = max_nc(m[qt], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m[qt] - m_new);
-            m[qt] = m_new;
-            u32 pw[4];
-            float lsum = 0.f;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const bf16x2 pk = {(__bf16)__builtin_amdgcn_exp2f(x[2 * k] - m_new),
-                                   (__bf16)__builtin_amdgcn_exp2f(x[2 * k + 1] - m_new)};
-                pw[k] = __builtin_bit_cast(u32, pk);
-                lsum += bf16_lo(pw[k]) + bf16_hi(pw[k]);  // the weights as V sees them
-            }
-            l[qt] = fmaf(l[qt], alpha, lsum);
-            const bf16x8 pt = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
-            // after the first pairs the running maximum rarely moves: rescale only when some column's did
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int jt = 0; jt < DB; ++jt) o[qt][jt] *= alpha;
-            }
-#pragma unroll
-            for (int jt = 0; jt < DB; ++jt)
-                o[qt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[jt]), pt, o[qt][jt], 0, 0, 0);
-        }
+        for (int qt = 0; qt < QT; ++qt)
+            MP::attend(kf, qf[qt], vf, kPageTokens, ntok1, gr, a.scale_log2, m[qt], l[qt], o[qt]);
     };
 
     // NBUF pair buffers in rotation: the loads of the next NBUF - 1 pairs are in flight while a pair is
@@ -552,27 +617,10 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
         }
     }
 
-    // partial of record p * n_live + rank, head hh: lane (gr, c) holds d in [4 DB gr, 4 DB gr + 4 DB)
+    // partials of the records p * n_live + rank
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        float ls = l[qt];
-        ls += __shfl_xor(ls, 16);
-        ls += __shfl_xor(ls, 32);
-        if (!valid[qt]) continue;
-        const size_t slot = ((size_t)p * n_live + rank_of[qt]) * a.Hkv + g;
-        float *pacc = a.part_acc + slot * ((size_t)G * D) + (size_t)hh_of[qt] * D + 4 * DB * gr;
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-            for (int j4 = 0; j4 < DB; j4 += 4)
-                *reinterpret_cast<float4 *>(pacc + DB * jj + j4) =
-                    make_float4(o[qt][j4][jj], o[qt][j4 + 1][jj], o[qt][j4 + 2][jj], o[qt][j4 + 3][jj]);
-        if (gr == 0) {
-            float *pml = a.part_ml + slot * ((size_t)G * 2) + hh_of[qt] * 2;
-            pml[0] = m[qt];
-            pml[1] = ls;
-        }
-    }
+    for (int qt = 0; qt < QT; ++qt)
+        MP::store_partial(a, ((size_t)p * n_live + rank_of[qt]) * a.Hkv + g, G, hh_of[qt], gr, valid[qt], m[qt], l[qt], o[qt]);
     if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
@@ -590,9 +638,10 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
 template <int D>
 __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
 {
-    constexpr int KB = D / 32, DB = D / 16, VW = DB / 2;
+    typedef MfmaPair<D> MP;
+    constexpr int KB = MP::KB, DB = MP::DB;
     constexpr int kBufs = 3;
-    typedef u32 VRow __attribute__((ext_vector_type(VW)));
+    typedef typename MP::VRow VRow;
     typedef u32 u32x4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
     const int g = blockIdx.x % a.Hkv;
@@ -700,70 +749,9 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
     uint4 qf[KB];
 
     auto attend_pair = [&](const uint4 (&kf)[2][KB], VRow (&vr)[8], int ntok0, int ntok1) {
-        const bool ragged = ntok0 < kPageTokens || ntok1 < kPageTokens;
-        if (ragged) {  // rows past the trace's last token may hold anything (NaN included)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (4 * gr + e >= ntok0) vr[e] = VRow(0);
-                if (4 * gr + e >= ntok1) vr[4 + e] = VRow(0);
-            }
-        }
         uint4 vf[DB];
-#pragma unroll
-        for (int jt = 0; jt < DB; ++jt) {
-            const u32 sel = (jt & 1) ? 0x07060302u : 0x05040100u;
-            u32 w[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) w[k] = __builtin_amdgcn_perm(vr[2 * k + 1][jt / 2], vr[2 * k][jt / 2], sel);
-            vf[jt] = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[0][kb]),
-                                                         __builtin_bit_cast(bf16x8, qf[kb]), s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[1][kb]),
-                                                         __builtin_bit_cast(bf16x8, qf[kb]), s1, 0, 0, 0);
-        }
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[e] = s0[e] * a.scale_log2;
-            x[4 + e] = s1[e] * a.scale_log2;
-        }
-        if (ragged) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (4 * gr + e >= ntok0) x[e] = -INFINITY;
-                if (4 * gr + e >= ntok1) x[4 + e] = -INFINITY;
-            }
-        }
-        float mx = x[0];
-#pragma unroll
-        for (int e = 1; e < 8; ++e) mx = max_nc(mx, x[e]);
-        mx = max_nc(mx, __shfl_xor(mx, 16));
-        mx = max_nc(mx, __shfl_xor(mx, 32));
-        const float m_new = max_nc(m, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
-        u32 pw[4];
-        float lsum = 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const bf16x2 pk = {(__bf16)__builtin_amdgcn_exp2f(x[2 * k] - m_new),
-                               (__bf16)__builtin_amdgcn_exp2f(x[2 * k + 1] - m_new)};
-            pw[k] = __builtin_bit_cast(u32, pk);
-            lsum += bf16_lo(pw[k]) + bf16_hi(pw[k]);  // the weights as V sees them
-        }
-        l = fmaf(l, alpha, lsum);
-        const bf16x8 pt = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-            for (int jt = 0; jt < DB; ++jt) o[jt] *= alpha;
-        }
-#pragma unroll
-        for (int jt = 0; jt < DB; ++jt)
-            o[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[jt]), pt, o[jt], 0, 0, 0);
+        MP::v_operands(vr, ntok0, ntok1, gr, vf);
+        MP::attend(kf, qf, vf, ntok0, ntok1, gr, a.scale_log2, m, l, o);
     };
 
     // pair buffers: tiles, the cursor they belong to and, for the first pair of a record, its queries
@@ -809,26 +797,7 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
             attend_pair(kf[b], vr[b], tokens_of(x.j), tokens_of(x.j + 1));
             const bool last = x.j + 2 >= n;
             fill(kf[b], vr[b], qslot[b], at[b]);  // the buffer is free: request the pair kBufs ahead
-            if (last) {  // the record's partial: lane (gr, c) holds d in [4 DB gr, 4 DB gr + 4 DB) of head c
-                float ls = l;
-                ls += __shfl_xor(ls, 16);
-                ls += __shfl_xor(ls, 32);
-                if (c < G) {
-                    const size_t slot = (size_t)x.id * a.Hkv + g;
-                    float *pacc = a.part_acc + slot * ((size_t)G * D) + (size_t)c * D + 4 * DB * gr;
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-                        for (int j4 = 0; j4 < DB; j4 += 4)
-                            *reinterpret_cast<float4 *>(pacc + DB * jj + j4) =
-                                make_float4(o[j4][jj], o[j4 + 1][jj], o[j4 + 2][jj], o[j4 + 3][jj]);
-                    if (gr == 0) {
-                        float *pml = a.part_ml + slot * ((size_t)G * 2) + c * 2;
-                        pml[0] = m;
-                        pml[1] = ls;
-                    }
-                }
-            }
+            if (last) MP::store_partial(a, (size_t)x.id * a.Hkv + g, G, min(c, G - 1), gr, c < G, m, l, o);
         }
     }
     if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
