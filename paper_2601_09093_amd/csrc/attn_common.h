@@ -73,6 +73,22 @@ __device__ __forceinline__ bool plan_usable(const AttnArgs &a)
 // max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
 __device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
 
+// Wave-uniform reads of data that no kernel of the same launch writes (records, block-table entries):
+// through the constant address space they become scalar loads, which have a counter of their own and
+// so do not queue behind the vector loads of the tile stream.
+__device__ __forceinline__ int32_t scalar_read(const int32_t *p)
+{
+    typedef const __attribute__((address_space(4))) int32_t *ConstPtr;
+    return *reinterpret_cast<ConstPtr>(reinterpret_cast<uintptr_t>(p));
+}
+__device__ __forceinline__ Record scalar_read(const Record *p)
+{
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(4))) i32x4 *ConstPtr;
+    const i32x4 v = *reinterpret_cast<ConstPtr>(reinterpret_cast<uintptr_t>(p));
+    return Record{v.x, v.y, v.z, v.w};
+}
+
 // Host-side launchers, one per translation unit.  D is the head dimension (64 or 128); e0 / e1, when
 // not null, are recorded at the start and the end of the stage-1 kernel (benchmarks only).
 void launch_plan(const AttnArgs &a, hipStream_t s);                                         // attn_plan.hip

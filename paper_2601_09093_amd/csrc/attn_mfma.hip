@@ -286,13 +286,15 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
 // (measured on a bare read probe: 6.79 against 6.81 TB/s), and the arithmetic per byte no longer grows
 // with G.  Page ids, records and tiles are requested ahead of their use across record boundaries:
 // the wave's page pairs form one sequence, a load cursor runs kBufs pairs ahead of the compute cursor.
+// (The compiler parks the second buffer in accumulator registers, which makes it wait for those loads
+// early; more buffers, or refills that always issue the same number of loads, measured no faster.)
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
 {
     typedef MfmaPair<D> MP;
     constexpr int KB = MP::KB, DB = MP::DB;
-    constexpr int kBufs = 3;
+    constexpr int kBufs = 2;
     typedef typename MP::VRow VRow;
     typedef u32 u32x4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
 
     bool bad_plan = false, bad_page = false;
     auto record_at = [&](int id) {  // a record that points outside the block tables is replaced and reported
-        Record x = a.records[id];
+        Record x = scalar_read(a.records + id);
         const bool ok = (u32)x.i < (u32)a.N && x.first >= 0 && x.n >= 1 && (long long)x.first + x.n <= a.MAXB &&
                         x.ntok >= 1 && x.ntok <= kPageTokens;
         bad_plan |= !ok;
@@ -355,8 +357,8 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
     };
     auto page_ids = [&](const Cursor &x, int &p0, int &p1) {  // second page of an odd record's last pair: the last page again
         const int32_t *row = a.block_tables + (size_t)x.rec.i * a.MAXB + x.rec.first;
-        p0 = row[x.j];
-        p1 = row[min(x.j + 1, x.rec.n - 1)];
+        p0 = scalar_read(row + x.j);
+        p1 = scalar_read(row + min(x.j + 1, x.rec.n - 1));
     };
 
     const size_t tile_bytes = (size_t)kPageTokens * D * 2;
@@ -421,7 +423,7 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
         load_pair(id0, id1, kfb, vrb);
         if (cur.j == 0) load_q(cur.rec.i, qb);
         advance(cur);
-        if (cur.id >= 0) page_ids(cur, id0, id1);  // used one refill later
+        if (cur.id >= 0) page_ids(cur, id0, id1);  // scalar loads, used one refill later
     };
 #pragma unroll
     for (int b = 0; b < kBufs; ++b) fill(kf[b], vr[b], qslot[b], at[b]);
