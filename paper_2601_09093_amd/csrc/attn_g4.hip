@@ -199,7 +199,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     // replaced by a one-token record of trace 0 and reported; nothing is read out of bounds
     bool bad_plan = false;
     auto record_at = [&](int id) {
-        Record x = a.records[id];
+        Record x = scalar_read(a.records + id);
         const bool ok = (u32)x.i < (u32)a.N && x.first >= 0 && x.n >= 1 && (long long)x.first + x.n <= a.MAXB &&
                         x.ntok >= 1 && x.ntok <= kPageTokens;
         bad_plan |= !ok;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     Record rec = record_at(rec_id);
     {
         const int32_t *bt0 = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
-        const size_t t0 = tile_at(bt0[0]), t1 = tile_at(bt0[rec.n > 1 ? 1 : 0]);
+        const size_t t0 = tile_at(scalar_read(bt0)), t1 = tile_at(scalar_read(bt0 + (rec.n > 1 ? 1 : 0)));
         load4(kbase, t0, k0);
         load4(vbase, t0, v0);
         load4(kbase, t1, k1);
@@ -226,14 +226,14 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         // record's pages
         const Record nrec = record_at(has_next ? next_id : rec_id);
         const int32_t *nbt = a.block_tables + (size_t)nrec.i * a.MAXB + nrec.first;
-        const int npage0 = nbt[0], npage1 = nbt[nrec.n > 1 ? 1 : 0];
+        const int npage0 = scalar_read(nbt), npage1 = scalar_read(nbt + (nrec.n > 1 ? 1 : 0));
 
         const int n = rec.n;
         const int32_t *bt = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
         // page ids are fetched one loop trip (two pages) ahead of the tile loads that need them; the
         // index is clamped so the pipeline can run past the end without a branch (the surplus load
         // re-reads the last tile, which is then not used)
-        auto page_id = [&](int j) { return bt[min(j, n - 1)]; };
+        auto page_id = [&](int j) { return scalar_read(bt + min(j, n - 1)); };
         auto ntok_of = [&](int j) { return j == n - 1 ? rec.ntok : kPageTokens; };
 
         m_own = kMinusBig; l_own = 0.f; mx_pending = kMinusBig;
