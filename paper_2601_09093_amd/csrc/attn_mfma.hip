@@ -180,7 +180,7 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
     };
     const int32_t *bt = a.shared_pages + first;  // first + n <= S <= kMaxShared
     auto page_at = [&](int j) {
-        const int pg = __builtin_amdgcn_readfirstlane(bt[min(j, n - 1)]);  // the same for every lane: keep it scalar
+        const int pg = scalar_read(bt + min(j, n - 1));  // written by attn_plan, the same for every lane
         const bool ok = (u32)pg < (u32)a.NP;
         bad_page |= !ok;
         return ok ? pg : 0;
