@@ -19,35 +19,8 @@ namespace {
 //      runs whose lengths top every wave up to Q pages; a run is one record per trace it touches.
 // ---------------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
+static_assert(kPlanThreads == 1024, "block_excl_scan works on 1024-thread workgroups");
 static_assert(kMaxShared <= kPlanThreads, "one thread copies one entry of the first live row");
-
-// exclusive scan of one int per thread over the workgroup (wave shuffles + 16 wave totals)
-__device__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
-{
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    int x = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int y = __shfl_up(x, off);
-        if (lane >= off) x += y;
-    }
-    if (lane == 63) scratch[wid] = x;
-    __syncthreads();
-    if (wid == 0) {
-        int t = lane < 16 ? scratch[lane] : 0;
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-            const int y = __shfl_up(t, off);
-            if (lane >= off) t += y;
-        }
-        if (lane < 16) scratch[16 + lane] = t;
-    }
-    __syncthreads();
-    const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
-    *total = scratch[31];
-    __syncthreads();
-    return base + x - v;
-}
 
 // in-place exclusive scan of arr[0..n), n <= 2 * kPlanThreads; returns the total
 __device__ int array_excl_scan(int *arr, int n, int *scratch)

@@ -51,6 +51,45 @@ constexpr int kDppRowRor4 = 0x124;
 constexpr int kDppRowRor8 = 0x128;
 #define STEP_DPP_QUAD_BCAST(k) ((k) * 0x55)
 
+// Order-preserving image of an fp32 score: a < b as floats <=> order_key(a) < order_key(b) as unsigned
+// (-0 counts as +0; NaN is the caller's business).
+__device__ __forceinline__ u32 order_key(float s)
+{
+    u32 u = __float_as_uint(s);
+    if (u == 0x80000000u) u = 0u;  // -0 == +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of one int per thread over a 1024-thread workgroup (wave shuffles, then the 16
+// wave totals); *total receives the sum.  scratch: 32 ints of LDS; the barrier at the start orders this
+// call's writes after the previous call's reads, so calls may follow each other directly.
+__device__ __forceinline__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
+{
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    __syncthreads();
+    if (lane == 63) scratch[wid] = x;
+    __syncthreads();
+    if (wid == 0) {
+        int t = lane < 16 ? scratch[lane] : 0;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const int y = __shfl_up(t, off);
+            if (lane >= off) t += y;
+        }
+        if (lane < 16) scratch[16 + lane] = t;
+    }
+    __syncthreads();
+    const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
+    *total = scratch[31];
+    return base + x - v;
+}
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? STEP_OK : STEP_ELAUNCH;

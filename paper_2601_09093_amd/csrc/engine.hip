@@ -19,14 +19,8 @@ namespace {
 
 typedef unsigned long long u64;
 constexpr int kThreads = 1024;
+static_assert(kThreads == 1024, "block_excl_scan works on 1024-thread workgroups");
 constexpr int kMaxN = 4096;
-
-__device__ __forceinline__ u32 order_key(float s)
-{
-    u32 u = __float_as_uint(s);
-    if (u == 0x80000000u) u = 0u;  // -0 == +0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
 
 // sum of one int per thread over the workgroup, returned to every thread
 __device__ int block_sum(int v, int *scratch /*[17]*/)
@@ -40,34 +34,6 @@ __device__ int block_sum(int v, int *scratch /*[17]*/)
 #pragma unroll
     for (int w = 0; w < kThreads / 64; ++w) t += scratch[w];
     return t;
-}
-
-// exclusive scan of one int per thread over the workgroup
-__device__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
-{
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    int x = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int y = __shfl_up(x, off);
-        if (lane >= off) x += y;
-    }
-    __syncthreads();
-    if (lane == 63) scratch[wid] = x;
-    __syncthreads();
-    if (wid == 0) {
-        int t = lane < 16 ? scratch[lane] : 0;
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-            const int y = __shfl_up(t, off);
-            if (lane >= off) t += y;
-        }
-        if (lane < 16) scratch[16 + lane] = t;
-    }
-    __syncthreads();
-    const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
-    *total = scratch[31];
-    return base + x - v;
 }
 
 struct ReserveArgs {

@@ -19,6 +19,7 @@ namespace {
 
 typedef unsigned long long u64;
 constexpr int kSelThreads = 1024;
+static_assert(kSelThreads == 1024, "block_excl_scan works on 1024-thread workgroups");
 constexpr int kMaxN = 4096;
 
 struct PruneHeader {  // first 256 bytes of the workspace
@@ -32,13 +33,6 @@ struct PruneArgs {
     u32 *bitmap;  // ceil(NP / 32) words
     int N, MAXB, NP, P, k, npad, words;
 };
-
-__device__ __forceinline__ u32 order_key(float s)
-{
-    u32 u = __float_as_uint(s);
-    if (u == 0x80000000u) u = 0u;  // -0 == +0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
 
 __global__ __launch_bounds__(kSelThreads) void prune_select(const PruneArgs a)
 {
@@ -153,33 +147,6 @@ __global__ __launch_bounds__(256) void prune_release(const PruneArgs a)
         }
     }
     *entry = -1;
-}
-
-// exclusive scan of one int per thread over the workgroup (wave shuffles + 16 wave totals)
-__device__ int block_excl_scan(int v, int *scratch /*[32]*/, int *total)
-{
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    int x = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int y = __shfl_up(x, off);
-        if (lane >= off) x += y;
-    }
-    if (lane == 63) scratch[wid] = x;
-    __syncthreads();
-    if (wid == 0) {
-        int t = lane < 16 ? scratch[lane] : 0;
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-            const int y = __shfl_up(t, off);
-            if (lane >= off) t += y;
-        }
-        if (lane < 16) scratch[16 + lane] = t;
-    }
-    __syncthreads();
-    const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
-    *total = scratch[31];
-    return base + x - v;
 }
 
 __global__ __launch_bounds__(kSelThreads) void prune_compact(const PruneArgs a)
