@@ -182,6 +182,23 @@ int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scor
                int32_t *freed_pages, int32_t *n_freed, void *workspace, size_t workspace_bytes,
                int32_t *status, void *stream);
 
+/*
+ * prune_free for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors
+ * as prune_free, without `workspace`: the scratch of the kernels (a 256-byte header and the freed-page
+ * bitmap, one bit per page) lives in a device array that is part of this library's code object,
+ * 512 KiB + 256 bytes, held by every GPU the library runs on until the process ends.  It covers pools
+ * of up to step_prune_static_max_pages() = 4194304 pages; a larger NP returns STEP_EWORKSPACE and
+ * nothing is enqueued.  The call allocates and frees nothing.  Its first call on a device looks up the
+ * array's address (not a stream operation; make that call outside graph capture).  All calls on one GPU
+ * share the array: two calls that overlap in time on one GPU (different streams) race on it; calls
+ * on one stream, or ordered by events, are safe, and every call clears what it needs cleared.
+ */
+int32_t step_prune_static_max_pages(void);
+int prune_free_static(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k,
+                      int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
+                      int32_t *freed_pages, int32_t *n_freed, int32_t *status, void *stream);
+
 /* ------------------------------------------------------------------------------------------ */
 /* Memory-triggered pruning + page allocation (Section 4.2; the GPUMemoryFull branch of         */
 /* Algorithm 1), the KV-cache write of NextToken, and WeightedVote (Section 4.3).               */
@@ -195,8 +212,8 @@ size_t step_reserve_workspace_bytes(int32_t N, int32_t MAXB, int32_t NP);
  * Before the next decode step: a live trace with seq_lens[i] % P == 0 needs a new page for its next
  * token.  While fewer pages are free (refcount 0) than traces need one, the live trace with the
  * smallest (scores[i], i) is pruned exactly as prune_free prunes one trace (pages released, row set
- * to -1, seq_len 0) -- "whenever GPU memory is full and the KV cache for the next decoding step
- * cannot be scheduled, prune the trace with the lowest average step score".  Then every trace that
+ * to -1, seq_len 0): the memory trigger of Section 4.2 / the GPUMemoryFull branch of Algorithm 1,
+ * read as "the pool cannot hold the pages the next decode step opens".  Then every trace that
  * still needs a page, in ascending index, takes the smallest free page id:
  * block_tables[i][seq_lens[i] / P] = page, refcounts[page] = 1, new_pages[i] = page.
  *

@@ -296,8 +296,8 @@ done:
 /* ------------------------------------------------------------------------ */
 
 /* Before the next decode step: a live trace whose length is a multiple of P
- * opens a new page with its next token.  "GPU memory is full and the KV cache
- * for the next decoding step cannot be scheduled" (Section 4.2) is read as:
+ * opens a new page with its next token.  Section 4.2's trigger (memory is
+ * full and the next step's KV cache does not fit) is read as:
  * fewer free pages (refcount 0) than traces that need one.  While that holds,
  * prune the live trace with the lowest score (ties: lowest index) and release
  * its pages, exactly as oracle_prune_free does for k = 1.  Then every trace

@@ -69,6 +69,10 @@ def lib():
     L.step_prune_workspace_bytes.argtypes = [i32, i32, i32]
     L.prune_free.restype = ctypes.c_int
     L.prune_free.argtypes = [i32, i32, i32, i32, vp, i32] + [vp] * 7 + [sz, vp, vp]
+    L.step_prune_static_max_pages.restype = i32
+    L.step_prune_static_max_pages.argtypes = []
+    L.prune_free_static.restype = ctypes.c_int
+    L.prune_free_static.argtypes = [i32, i32, i32, i32, vp, i32] + [vp] * 6 + [vp, vp]
     L.step_reserve_workspace_bytes.restype = sz
     L.step_reserve_workspace_bytes.argtypes = [i32, i32, i32]
     L.step_reserve_pages.restype = ctypes.c_int
@@ -232,6 +236,21 @@ def prune_free(scores, k, refcounts, block_tables, seq_lens, pruned=None, freed_
         _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _dev(status, i32, "status", True), _stream())
     if rc != STEP_OK:
         raise StepError(rc, "prune_free")
+    return pruned, freed_pages, n_freed
+
+
+def prune_free_static(scores, k, refcounts, block_tables, seq_lens, pruned, freed_pages, n_freed, status=None, P=16):
+    """prune_free with the library's own static scratch: no workspace, nothing allocated (outputs are the caller's)."""
+    N, MAXB = block_tables.shape
+    NP = refcounts.numel()
+    i32 = (torch.int32,)
+    rc = lib().prune_free_static(
+        N, MAXB, NP, int(P), _dev(scores, (torch.float32,), "scores"), int(k), _dev(refcounts, i32, "refcounts"),
+        _dev(block_tables, i32, "block_tables"), _dev(seq_lens, i32, "seq_lens"), _dev(pruned, i32, "pruned"),
+        _dev(freed_pages, i32, "freed_pages"), _dev(n_freed, i32, "n_freed"), _dev(status, i32, "status", True),
+        _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "prune_free_static")
     return pruned, freed_pages, n_freed
 
 

@@ -114,6 +114,15 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     float m[G], acc[G][8];
     float m_own, l_own, mx_pending;
 
+    // The lanes of a row group exchange their weights through pbuf: lane l writes word l, the group's other
+    // lanes read it.  A single wave's LDS operations retire in order; these fences and the wave barrier
+    // (no instructions) also forbid the compiler to move the reads and writes across the exchange points.
+    auto wave_lds_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
     auto phaseA = [&](const uint4 (&k)[IPP], int slot, int ntok) {
         float val[NV];
 #pragma unroll
@@ -146,7 +155,9 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         const bf16x2 pk = {(__bf16)p, (__bf16)p_next};
         const u32 w = __builtin_bit_cast(u32, pk);
         l_own = fmaf(l_own, alpha_own, bf16_lo(w));
+        wave_lds_sync();  // the reads of this slot two pages ago come first
         pbuf[slot][lane] = w;
+        wave_lds_sync();  // the row group's reads of this slot come after
     };
 
     auto pv_pairs = [&](const uint4 (&v)[IPP], int slot) {

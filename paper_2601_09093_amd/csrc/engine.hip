@@ -1,8 +1,8 @@
 // The pieces of Algorithm 1 around the three hot calls, so that a whole multi-step decode loop
 // runs on the device without a host round trip:
 //   step_reserve_pages  Section 4.2's trigger.  Before the next decode step a live trace whose
-//                       length is a multiple of P needs a new page.  "GPU memory is full and the KV
-//                       cache for the next decoding step cannot be scheduled" = fewer free pages
+//                       length is a multiple of P needs a new page.  The trigger (memory full, the
+//                       next step's KV cache does not fit) is read as: fewer free pages
 //                       (refcount 0) than traces that need one; while that holds, the live trace
 //                       with the lowest score is pruned and its pages released (Algorithm 1:
 //                       argmin, ReleaseKVCache, T <- T \ {t*}), one trace at a time.  Then every

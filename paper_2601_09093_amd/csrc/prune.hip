@@ -12,6 +12,8 @@
 // prune_compact: one workgroup scans the bitmap in ascending page order (popcount + prefix sum)
 //                and writes the freed page ids; then marks the pruned traces dead.
 // prune_fused  : all of the above in one workgroup, for small problems.
+#include <mutex>
+
 #include "common.h"
 
 namespace step {
@@ -307,23 +309,19 @@ extern "C" size_t step_prune_workspace_bytes(int32_t N, int32_t MAXB, int32_t NP
     return 256 + ((words * sizeof(u32) + 255) & ~(size_t)255);
 }
 
-extern "C" int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k,
-                          int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
-                          int32_t *freed_pages, int32_t *n_freed, void *workspace, size_t workspace_bytes,
-                          int32_t *status, void *stream)
-{
-    if (N < 0 || N > kMaxN || MAXB < 0 || NP < 0 || P <= 0 || k < 0 || k > N) return STEP_EINVAL;
-    if (!n_freed) return STEP_EINVAL;
-    if (N > 0 && (!scores || !seq_lens || !block_tables || !refcounts)) return STEP_EINVAL;
-    if (k > 0 && (!pruned || !freed_pages)) return STEP_EINVAL;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < step_prune_workspace_bytes(N, MAXB, NP))
-        return STEP_EWORKSPACE;
+namespace {
 
+// Shared by prune_free (scratch = the caller's workspace) and prune_free_static (scratch = this
+// library's own device array): argument checks, then the launches.  `scratch` is a device address.
+int run_prune(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k, int32_t *refcounts,
+              int32_t *block_tables, int32_t *seq_lens, int32_t *pruned, int32_t *freed_pages, int32_t *n_freed,
+              void *scratch, int32_t *status, void *stream)
+{
     PruneArgs a;
     a.scores = scores; a.refcounts = refcounts; a.block_tables = block_tables; a.seq_lens = seq_lens;
     a.pruned = pruned; a.freed_pages = freed_pages; a.n_freed = n_freed; a.status = status;
-    a.hdr = reinterpret_cast<PruneHeader *>(workspace);
-    a.bitmap = reinterpret_cast<u32 *>(reinterpret_cast<char *>(workspace) + 256);
+    a.hdr = reinterpret_cast<PruneHeader *>(scratch);
+    a.bitmap = reinterpret_cast<u32 *>(reinterpret_cast<char *>(scratch) + 256);
     a.N = N; a.MAXB = MAXB; a.NP = NP; a.P = P; a.k = k;
     a.npad = 2;
     while (a.npad < N) a.npad <<= 1;
@@ -340,4 +338,76 @@ extern "C" int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const 
         hipLaunchKernelGGL(prune_release, dim3((MAXB + 255) / 256, k), dim3(256), 0, s, a);
     hipLaunchKernelGGL(prune_compact, dim3(1), dim3(kSelThreads), 0, s, a);
     return launch_status();
+}
+
+bool prune_args_ok(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k,
+                   const int32_t *refcounts, const int32_t *block_tables, const int32_t *seq_lens,
+                   const int32_t *pruned, const int32_t *freed_pages, const int32_t *n_freed)
+{
+    if (N < 0 || N > kMaxN || MAXB < 0 || NP < 0 || P <= 0 || k < 0 || k > N) return false;
+    if (!n_freed) return false;
+    if (N > 0 && (!scores || !seq_lens || !block_tables || !refcounts)) return false;
+    if (k > 0 && (!pruned || !freed_pages)) return false;
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// prune_free_static: the scratch of the three-kernel path (header + freed-page bitmap) lives in a
+// device array of this library instead of a caller's workspace, for callers that cannot allocate.
+// Every GPU holds its own copy of the array at its own address; the address is looked up once per
+// device and kept.  The array's name is never used as a pointer in host code.
+// ---------------------------------------------------------------------------------------------
+constexpr int kStaticMaxNP = 1 << 22;  // pages the static bitmap covers (512 KiB + the 256-byte header)
+static __device__ __align__(256) unsigned char scratch[256 + kStaticMaxNP / 8];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, nullptr until looked up
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return STEP_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return STEP_ELAUNCH;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return STEP_OK;
+}
+
+}  // namespace
+
+extern "C" int prune_free(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k,
+                          int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
+                          int32_t *freed_pages, int32_t *n_freed, void *workspace, size_t workspace_bytes,
+                          int32_t *status, void *stream)
+{
+    if (!prune_args_ok(N, MAXB, NP, P, scores, k, refcounts, block_tables, seq_lens, pruned, freed_pages, n_freed))
+        return STEP_EINVAL;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < step_prune_workspace_bytes(N, MAXB, NP))
+        return STEP_EWORKSPACE;
+    return run_prune(N, MAXB, NP, P, scores, k, refcounts, block_tables, seq_lens, pruned, freed_pages, n_freed,
+                     workspace, status, stream);
+}
+
+extern "C" int32_t step_prune_static_max_pages(void) { return kStaticMaxNP; }
+
+extern "C" int prune_free_static(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores, int32_t k,
+                                 int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
+                                 int32_t *freed_pages, int32_t *n_freed, int32_t *status, void *stream)
+{
+    if (!prune_args_ok(N, MAXB, NP, P, scores, k, refcounts, block_tables, seq_lens, pruned, freed_pages, n_freed))
+        return STEP_EINVAL;
+    if (NP > kStaticMaxNP) return STEP_EWORKSPACE;  // the pool is larger than the static bitmap covers
+    void *ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != STEP_OK) return rc;
+    return run_prune(N, MAXB, NP, P, scores, k, refcounts, block_tables, seq_lens, pruned, freed_pages, n_freed, ptr,
+                     status, stream);
 }

@@ -197,7 +197,11 @@ _CFG = {
     2: dict(N=16, Hq=32, Hkv=8, D=128, prompt=512, tail=(4096, 16384), slack=1.0, scorer=(4096, 1024, 4, 0), k=0, layers=1),
     3: dict(N=64, Hq=32, Hkv=8, D=128, prompt=1024, tail=(8192, 32768), slack=1.25, scorer=(4096, 1024, 4, 0), k=0, layers=1),
     4: dict(N=128, Hq=32, Hkv=8, D=128, prompt=1024, tail=None, slack=1.0, scorer=(4096, 1024, 13, 0), k=0, layers=36),
-    5: dict(N=256, Hq=32, Hkv=8, D=128, prompt=1024, tail=None, slack=1.0, scorer=(4096, 1024, 26, 0), k=64, layers=1),
+    # config 5's scorer inputs have a seed of their own, re-drawn (0x5EED0005 + 0x100 j, j = 0, 1, ...) until the
+    # independent float64 chain leaves a gap above 4e-3 between the 64th and 65th lowest trace score, so that
+    # the pruned set does not hinge on the scorer's last bits; tests/golden/pick_config5_scorer_seed.py finds j = 5
+    5: dict(N=256, Hq=32, Hkv=8, D=128, prompt=1024, tail=None, slack=1.0, scorer=(4096, 1024, 26, 0), k=64, layers=1,
+            scorer_seed=0x5EED0505),
 }
 
 
@@ -243,6 +247,7 @@ def make_workload(cfg: int, *, kv: bool = True, poison: bool = False, permute: b
         sc = build_scorer(seed, Nn, 8, d, m, 8, act, trace_of=np.arange(8, dtype=np.int32) % Nn)
     else:
         B = min(B, Nn) if N is not None else B
-        sc = build_scorer(seed, Nn, Nn, d, m, B, act, prior_state=(cfg == 5))
+        sc = build_scorer(c.get("scorer_seed", seed) if seed == 0x5EED0000 + cfg else seed, Nn, Nn, d, m, B, act,
+                          prior_state=(cfg == 5))
     k = c["k"] if N is None else (c["k"] * Nn) // c["N"]
     return Workload("config%d" % cfg, seed, shape, layout, q, k_pages, v_pages, sc, k, c["layers"])

@@ -15,10 +15,11 @@ TOL = 2e-2
 P = 16
 
 
-def test_config4_full_sweep_sampled_layers():
+def test_config4_full_sweep_three_layers_every_row():
     """Config 4 at full size: 36 layers, N = 128 traces with lognormal lengths, ~210 GB of bf16 KV
     drawn on the device, one plan for the step, 36 attention calls; parity on layers 0, 17 and 35
-    for sampled (trace, head) rows.  Skipped when the device does not have the memory free."""
+    for every (trace, head) row (that layer's K/V pool is read back for the oracle).  Skipped when
+    the device does not have the memory free."""
     w = wl.make_workload(4, kv=False)
     lay, s = w.layout, w.shape
     layers = w.layers
@@ -40,22 +41,16 @@ def test_config4_full_sweep_sampled_layers():
         binding.paged_decode_attn_planned(qs[l], ks[l], vs[l], bt, sl, outs[l], ws, status=st)
     torch.cuda.synchronize()
     assert int(st.item()) == 0
-    order = np.argsort(lay.seq_lens)
-    traces = np.unique([order[0], order[-1], order[len(order) // 2]])
-    heads = np.arange(s.Hkv) * (s.Hq // s.Hkv) + (np.arange(s.Hkv) % (s.Hq // s.Hkv))
-    pages = np.unique(np.concatenate([lay.block_tables[t][: (lay.seq_lens[t] + P - 1) // P] for t in traces]))
-    remap = -np.ones(lay.NP, np.int64); remap[pages] = np.arange(pages.size)
-    idx = torch.from_numpy(pages).to(DEV)
-    btr = np.where(lay.block_tables[traces] >= 0, remap[np.maximum(lay.block_tables[traces], 0)], -1).astype(np.int32)
-    slr = lay.seq_lens[traces].copy()
-    rows = (np.repeat(np.arange(traces.size), heads.size).astype(np.int32), np.tile(heads, traces.size).astype(np.int32))
     for l in (0, 17, 35):
+        print("config 4: oracle on layer %d, all %d x %d rows" % (l, s.N, s.Hq), flush=True)
         got = host_f32_of_bf16(outs[l])
-        assert np.all(np.isfinite(got))
-        kh = host_bits(ks[l].index_select(0, idx)); vh = host_bits(vs[l].index_select(0, idx))
-        qh = np.ascontiguousarray(host_bits(qs[l])[traces])
-        want = oracle.paged_decode_attn(qh, kh, vh, btr, slr, rows=rows)
-        err = np.abs(got[traces][rows[0], rows[1]] - want)
-        assert err.max() <= TOL, (l, float(err.max()))
+        want = oracle.paged_decode_attn(host_bits(qs[l]), host_bits(ks[l]), host_bits(vs[l]), lay.block_tables,
+                                        lay.seq_lens)
+        err = np.abs(got - want)
+        assert np.all(np.isfinite(got)) and err.max() <= TOL, (l, float(err.max()))
+        assert np.all(err <= 2.0 ** -8 * np.abs(want) + 4e-3), (l, float(err.max()))
+    for l in range(layers):    # the other layers: finite, inside the value range of a convex combination
+        got = host_f32_of_bf16(outs[l])
+        assert np.all(np.isfinite(got)) and np.abs(got).max() < 6.0, l
     del ks, vs
     torch.cuda.empty_cache()

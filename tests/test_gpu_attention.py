@@ -333,43 +333,31 @@ def test_full_config2():
 
 def _device_kv(NP, Hkv, D, seed):
     g = torch.Generator(device=DEV); g.manual_seed(seed)
-    k = torch.randn((NP, Hkv, P, D), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
-    v = torch.randn((NP, Hkv, P, D), generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.empty((NP, Hkv, P, D), dtype=torch.bfloat16, device=DEV).normal_(generator=g)
+    v = torch.empty((NP, Hkv, P, D), dtype=torch.bfloat16, device=DEV).normal_(generator=g)
     return k, v
 
 
-@pytest.mark.parametrize("cfg", [3, 5])
-def test_full_size_sampled_rows(cfg):
-    """Configs 3 and 5 at full size, in the launch configuration bench.py times: K/V are drawn on
-    the device, a sample of (trace, head) rows is recomputed by the oracle from the bytes it reads
-    back, and every row is checked for finiteness and for staying inside the value range."""
-    w = wl.make_workload(cfg, kv=False)
+def test_full_config3_every_row():
+    """Config 3 (the headline workload) at full size, in the launch configuration bench.py times: K/V
+    are drawn on the device (about 6.5 GB), read back, and every one of the 64 x 32 output rows is
+    compared with the float64 oracle, element by element.  (Config 5 at full size: tests/test_gpu_chain.py;
+    config 4: tests/test_gpu_a_config4_sweep.py.)"""
+    w = wl.make_workload(3, kv=False)
     lay, s = w.layout, w.shape
     k, v = _device_kv(lay.NP, s.Hkv, s.D, w.seed)
     st = new_status()
-    tq = dev_bits(w.q)
-    out = binding.paged_decode_attn(tq, k, v, dev(lay.block_tables), dev(lay.seq_lens), status=st)
+    out = binding.paged_decode_attn(dev_bits(w.q), k, v, dev(lay.block_tables), dev(lay.seq_lens), status=st)
     torch.cuda.synchronize()
     assert int(st.item()) == 0
     got = host_f32_of_bf16(out)
-    assert np.all(np.isfinite(got))
-    assert np.abs(got).max() < 6.0                                 # convex combination of N(0,1) bf16 values
-    # sample: shortest, longest and two more traces; one query head per KV head; remap their pages
-    order = np.argsort(lay.seq_lens)
-    traces = np.unique([order[0], order[-1], order[len(order) // 2], order[1]])
-    heads = np.arange(s.Hkv) * (s.Hq // s.Hkv) + (np.arange(s.Hkv) % (s.Hq // s.Hkv))
-    pages = np.unique(np.concatenate([lay.block_tables[t][: (lay.seq_lens[t] + P - 1) // P] for t in traces]))
-    remap = -np.ones(lay.NP, np.int64); remap[pages] = np.arange(pages.size)
-    idx = torch.from_numpy(pages).to(DEV)
-    ks = host_bits(k.index_select(0, idx)); vs = host_bits(v.index_select(0, idx))
-    bt = np.where(lay.block_tables[traces] >= 0, remap[np.maximum(lay.block_tables[traces], 0)], -1).astype(np.int32)
-    sl = lay.seq_lens[traces].copy()
-    rows = (np.repeat(np.arange(traces.size), heads.size).astype(np.int32), np.tile(heads, traces.size).astype(np.int32))
-    want = oracle.paged_decode_attn(np.ascontiguousarray(w.q[traces]), ks, vs, bt, sl, rows=rows)
-    sel = got[traces][rows[0], rows[1]]
-    err = np.abs(sel - want)
-    assert err.max() <= TOL
+    kh, vh = host_bits(k), host_bits(v)
+    del k, v
+    want = oracle.paged_decode_attn(w.q, kh, vh, lay.block_tables, lay.seq_lens)
+    err = np.abs(got - want)
+    assert np.all(np.isfinite(got)) and err.max() <= TOL, float(err.max())
     assert np.all(err <= 2.0 ** -8 * np.abs(want) + 4e-3), float(err.max())
+    torch.cuda.empty_cache()
 
 
 def test_one_plan_shared_by_several_layers():

@@ -75,6 +75,36 @@ def test_no_boundaries_still_refreshes_scores():
     assert np.array_equal(scores, want) and np.isposinf(scores[2])
 
 
+def test_running_mean_division_is_the_correctly_rounded_quotient():
+    """The hand cases of tests/golden/running_mean_hand.json that have no boundaries (B = 0) through step_score:
+    their quotients (41/41, 20.5/41, 21/7 ...) are exact, and a reciprocal-then-multiply evaluation would miss them
+    by one unit in the last place (Section 4.3 equation).  Then one with boundaries whose step score is exactly
+    0.5 (W1 = 0, b1 = 0, b2 = 0): 20 + 0.5 over 41 steps is 0.5."""
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "running_mean_hand.json")))
+    ran = 0
+    for c in g["cases"]:
+        if c["probs"]:
+            continue
+        N = c["N"]
+        s = wl.build_scorer(82, N, N, 256, 64, 0, 0)
+        s.score_sum = np.array(c["sum0"], np.float32); s.score_cnt = np.array(c["cnt0"], np.int32)
+        _, _, ssum, cnt, scores = run_gpu(s, N)
+        want = np.array([np.inf if x == "inf" else x for x in c["scores"]], np.float32)
+        assert np.array_equal(scores, want), (scores, want)
+        assert np.array_equal(ssum, np.array(c["sum"], np.float32)) and np.array_equal(cnt, np.array(c["cnt"], np.int32))
+        ran += 1
+    assert ran >= 2
+    s = wl.build_scorer(83, 3, 3, 256, 64, 3, 0)
+    s.W1[:] = 0; s.b1[:] = 0; s.b2 = 0.0
+    s.trace_of = np.array([0, 1, 2], np.int32)
+    s.score_sum = np.array([20.0, 23.0, 27.0], np.float32); s.score_cnt = np.array([40, 46, 54], np.int32)
+    lo, pr, ssum, cnt, scores = run_gpu(s, 3)
+    assert np.all(lo == 0) and np.all(pr == np.float32(0.5))
+    assert np.array_equal(ssum, np.array([20.5, 23.5, 27.5], np.float32)) and cnt.tolist() == [41, 47, 55]
+    assert np.array_equal(scores, np.full(3, 0.5, np.float32))
+
+
 def test_logits_only_without_state():
     s = wl.build_scorer(79, 4, 4, 512, 64, 3, 1)
     lo, pr, *_ = run_gpu(s, 4, with_state=False)
