@@ -23,7 +23,8 @@ def test_header_declares_the_three_calls():
               "step_score_workspace_bytes", "step_prune_workspace_bytes", "step_strerror", "step_version",
               "step_calib_copy", "step_attn_profile_begin", "step_attn_profile_end",
               "step_attn_waves_per_head", "step_attn_plan", "paged_decode_attn_planned",
-              "step_reserve_workspace_bytes", "step_reserve_pages", "step_append_kv", "step_weighted_vote"):
+              "step_reserve_workspace_bytes", "step_reserve_pages", "step_append_kv", "step_weighted_vote",
+              "prune_free_static", "step_prune_static_max_pages"):
         assert n in names, names
 
 
