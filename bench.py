@@ -239,16 +239,16 @@ def main():
     # ---- roofline of the dominant kernel (attention stage 1) --------------------------------
     nb = (lay.seq_lens.astype(np.int64) + s.P - 1) // s.P
     G = s.Hq // s.Hkv
-    hdr = ws_attn[:64].view(torch.int32).cpu().tolist()              # plan header written by the planning kernel
-    records, n1, n_live, shared_pages, prefix_mfma = hdr[0], hdr[1], hdr[2], hdr[4], hdr[8]
-    # with the shared prompt on the matrix cores (its own small kernel), stage 1 streams the private pages only
-    stage1_records = records - n1 if prefix_mfma else records
-    stage1_tokens = lay.unique_tokens - (shared_pages * s.P if prefix_mfma else 0)
-    items = stage1_records * s.Hkv
+    hdr = ws_attn[:64].view(torch.int32).cpu().tolist()              # figures of the cut left by the streaming kernel
+    pieces, private_pages, quota, prefix_slots, shared_pages = hdr[1], hdr[2], hdr[3], hdr[4], hdr[5]
+    n_live = int((lay.seq_lens > 0).sum())
+    assert private_pages == int(nb.sum()) - n_live * shared_pages, "per-block shared prefixes differ: not this workload"
+    # the shared prompt runs on the matrix cores (attn_front); stage 1 streams the private pages only
+    stage1_tokens = lay.requested_tokens - n_live * shared_pages * s.P
     alg_bytes = (stage1_tokens * s.kv_bytes_per_token               # every KV byte stage 1 is responsible for, once
-                 + (int(nb.sum()) - (shared_pages * n_live if prefix_mfma else 0)) * 4   # block-table entries
+                 + private_pages * 4                                # block-table entries
                  + s.N * s.Hq * s.D * 2                             # q
-                 + items * G * (s.D + 2) * 4)                       # split-K partials written by stage 1
+                 + pieces * s.Hkv * G * (s.D + 2) * 4)              # split-K partials written by stage 1
     # the "requested" variant counts every trace's own view of its context (the shared prompt N times)
     req_bytes = alg_bytes + (lay.requested_tokens - lay.unique_tokens) * s.kv_bytes_per_token
     avg_ms = float(np.mean(stage1_ms))
@@ -273,7 +273,7 @@ def main():
                    "unique_kv_tokens": lay.unique_tokens, "pool_pages": lay.NP, "scorer": "%d->%d->1 %s, B=%d" % (
                        sc.hidden.shape[1], sc.W1.shape[0], "ReLU" if sc.act == 0 else "GELU", B),
                    "prune_k": prune_k, "attn_waves_per_kv_head": binding.attn_waves_per_head(adims),
-                   "attn_records": records, "shared_prefix_pages_on_mfma": shared_pages if prefix_mfma else 0,
+                   "attn_records": pieces, "attn_pages_per_wave": quota, "shared_prefix_pages_on_mfma": shared_pages,
                    "mode": args.mode, "launch": "hip-graph" if args.graph else "stream"},
         "attn_hbm_gbs": round(achieved, 1), "attn_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
         "roofline": roofline,

@@ -2,17 +2,15 @@
 // KV cache -- the attention inside NextToken(t) of Algorithm 1 (the paper gives no formula; this
 // is softmax(q K^T scale) V for the newest token of every live trace).
 //
-// Four kernels per call:
-//   attn_plan    one workgroup.  Validates the lengths, finds the leading pages that every live trace
-//                shares (the prompt), and cuts the work into records (trace, first page, page count,
-//                tokens in the last page): the shared pages into sub-chunks, the private pages of all
-//                traces, concatenated, into one equal run per resident wave.
-//   attn_prefix  the shared pages on the matrix cores: for one KV head the query rows of all live
-//                traces form a dense matrix, so logits and output are two MFMA products and every
-//                shared tile is read once per block of query rows instead of once per trace.
+// Three kernels per call (how the work is cut: attn_common.h):
+//   attn_front   the pages shared by the live traces of a block of traces (the prompt) on the matrix cores:
+//                for one KV head the query rows of the block form a dense matrix, so logits and output are
+//                two MFMA products and every shared tile is read once per block instead of once per trace.
+//                Each wave finds its block's shared-prefix length S_b by itself and stores it.
 //   stage 1      the HBM-streaming kernels over the private pages: persistent single-wave workgroups,
-//                one per resident wave slot, each walking its own list of records with the loads of the
-//                next pages (and of the next record) in flight.
+//                one per resident wave slot.  Every wave works out, from seq_lens and the S_b, the equal
+//                share of the concatenated private pages that is its own (no planning kernel, no record
+//                array) and walks it with the loads of the next pages (and of the next record) in flight.
 //                attn_partial_g4 (G == 4, D == 128): a (page, head) tile is P*D bf16 contiguous; the
 //                wave reads it with 16-byte loads, lane l taking bytes [j*1024 + 16 l, +16) on load j.  A row of D
 //                values lives in LPR = D/8 neighbouring lanes and each group of LPR lanes ("row group"
@@ -21,11 +19,11 @@
 //                register (bf16 dot2 on the vector ALUs).
 //                attn_partial_mfma (every other shape): the two products on the matrix cores with the G
 //                query heads of the trace in the columns, so the arithmetic per byte does not grow with G.
-//   attn_merge   stage 2: per (trace, query head) combine the record partials (m, l, acc), round to
-//                bf16.
-// Files: attn_common.h (plan and argument structs, launcher declarations), attn_plan.hip, attn_mfma.hip
-// (attn_prefix, attn_partial_mfma), attn_g4.hip (attn_partial_g4), attn_merge.hip, and this file: argument
-// checks, the workspace layout, the launch sequence and the C entry points.
+//   attn_merge   stage 2: per (trace, query head) combine the partials (m, l, acc) of its shared-prefix
+//                sub-chunks and of its private-page records, round to bf16.
+// Files: attn_common.h (argument struct, the cut, launcher declarations), attn_mfma.hip (attn_front,
+// attn_partial_mfma), attn_g4.hip (attn_partial_g4), attn_merge.hip, and this file: argument checks, the
+// workspace layout, the launch sequence and the C entry points.
 #include "attn_common.h"
 
 namespace step {
@@ -44,6 +42,7 @@ bool dims_ok(const step_attn_dims *d)
     const int G = d->Hq / d->Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return false;
     if (d->N > kMaxPlanN) return false;
+    if ((long long)d->N * d->MAXB >= (1ll << 30)) return false;  // page counts are summed in 32 bits
     return true;
 }
 
@@ -85,8 +84,8 @@ bool prefix_enabled()
 }
 
 struct Layout {  // byte offsets into the workspace, all multiples of 256
-    size_t off2, records, rank, first2, cnt2, live, shared_pages, ml, acc, total;
-    int Wh, max_records;
+    size_t blk_shared, first2, cnt2, ml, acc, total;
+    int Wh, TB, nblk, pmax, max_slots, prefix_qt;
 };
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -94,18 +93,21 @@ size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 Layout layout_for(const step_attn_dims *d)
 {
     Layout l;
+    const int G = d->Hq / d->Hkv;
     l.Wh = waves_per_head(d);
-    // private pages: at most Wh + N records; shared prefix: at most 4 Wh + N (attn_prefix), Wh + N otherwise
-    l.max_records = 6 * l.Wh + 2 * d->N;
-    const size_t R = (size_t)l.max_records, G = d->Hq / d->Hkv, N = d->N;
-    l.off2 = 256;
-    l.records = l.off2 + up256((size_t)(l.Wh + 1) * sizeof(int32_t));
-    l.rank = l.records + up256(R * sizeof(Record));
-    l.first2 = l.rank + up256(N * sizeof(int32_t));
+    // query tiles per wave of attn_front: 2 once there are enough query rows to fill the chip that way
+    l.prefix_qt = !prefix_enabled() ? 0 : ((long long)d->N * G >= 256) ? 2 : 1;
+    l.TB = 16 * (l.prefix_qt ? l.prefix_qt : 1) / G;
+    l.nblk = (d->N + l.TB - 1) / l.TB;
+    // sub-chunks of a shared prefix per trace: N * pmax <= 4 Wh + N partial slots
+    l.pmax = 1 + 4 * l.Wh / (d->N > 0 ? d->N : 1);
+    if (l.pmax > kMaxParts) l.pmax = kMaxParts;
+    l.max_slots = d->N * l.pmax + d->N + l.Wh;  // private pages: at most one record per trace and one more per wave
+    const size_t R = (size_t)l.max_slots, N = d->N;
+    l.blk_shared = 256;
+    l.first2 = l.blk_shared + up256((size_t)(l.nblk > 0 ? l.nblk : 1) * sizeof(int32_t));
     l.cnt2 = l.first2 + up256(N * sizeof(int32_t));
-    l.live = l.cnt2 + up256(N * sizeof(int32_t));
-    l.shared_pages = l.live + up256(N * sizeof(int32_t));
-    l.ml = l.shared_pages + up256(kMaxShared * sizeof(int32_t));
+    l.ml = l.cnt2 + up256(N * sizeof(int32_t));
     l.acc = l.ml + up256(R * d->Hkv * G * 2 * sizeof(float));
     l.total = l.acc + up256(R * d->Hkv * G * d->D * sizeof(float));
     return l;
@@ -121,9 +123,10 @@ enum : int { kDoPlan = 1, kDoAttend = 2 };
 
 int launch(const AttnArgs &a, int D, hipStream_t s, int what)
 {
-    if (what & kDoPlan) launch_plan(a, s);
+    if (what == kDoPlan) launch_plan_blocks(a, s);
     if (what & kDoAttend) {
-        launch_prefix(a, D, s);
+        // one call: every wave of attn_front finds its block's shared prefix itself; planned: they are in the workspace
+        launch_front(a, D, (what & kDoPlan) != 0, s);
         // when profiling, the stage-1 launch carries its own start/stop events: they take the
         // kernel's begin and end timestamps, with no marker processing inside the interval
         const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
@@ -163,23 +166,18 @@ int run(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages, con
     a.q = q; a.k_pages = k_pages; a.v_pages = v_pages;
     a.block_tables = block_tables; a.seq_lens = seq_lens;
     a.hdr = reinterpret_cast<PlanHeader *>(ws);
-    a.off2 = reinterpret_cast<int32_t *>(ws + l.off2);
-    a.records = reinterpret_cast<Record *>(ws + l.records);
-    a.rank = reinterpret_cast<int32_t *>(ws + l.rank);
+    a.blk_shared = reinterpret_cast<int32_t *>(ws + l.blk_shared);
     a.first2 = reinterpret_cast<int32_t *>(ws + l.first2);
     a.cnt2 = reinterpret_cast<int32_t *>(ws + l.cnt2);
-    a.live = reinterpret_cast<int32_t *>(ws + l.live);
-    a.shared_pages = reinterpret_cast<int32_t *>(ws + l.shared_pages);
     a.part_ml = reinterpret_cast<float *>(ws + l.ml);
     a.part_acc = reinterpret_cast<float *>(ws + l.acc);
     a.out = out; a.status = status;
     a.N = d->N; a.Hq = d->Hq; a.Hkv = d->Hkv; a.MAXB = d->MAXB; a.NP = d->NP;
-    a.Wh = l.Wh; a.max_records = l.max_records;
-    // query tiles per prefix wave: 2 once there are enough query rows to fill the chip that way
-    a.prefix_qt = !prefix_enabled() ? 0 : ((long long)d->N * (d->Hq / d->Hkv) >= 256) ? 2 : 1;
+    a.Wh = l.Wh; a.TB = l.TB; a.nblk = l.nblk; a.pmax = l.pmax; a.max_slots = l.max_slots;
+    a.prefix_qt = l.prefix_qt;
     // never 0, so a cleared workspace never passes for a plan
     a.stamp = (int)((0x5157u ^ ((u32)d->N * 2654435761u) ^ ((u32)d->MAXB * 40503u) ^ ((u32)d->NP * 2246822519u) ^
-                     ((u32)d->Hkv << 24) ^ ((u32)l.Wh << 12) ^ ((u32)a.prefix_qt << 8)) | 1u);
+                     ((u32)d->Hkv << 24) ^ ((u32)l.Wh << 12) ^ ((u32)a.prefix_qt << 8) ^ ((u32)d->Hq << 4)) | 1u);
     a.scale_log2 = d->scale * 1.4426950408889634f;
 
     return launch(a, d->D, reinterpret_cast<hipStream_t>(stream), what);

@@ -49,35 +49,19 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     static_assert(D == 128 && NV == LPR, "a row is 16 lanes wide: one logit per lane after the transposing reduction");
     constexpr int NPAIR = IPP / 2;  // token pairs per lane per page
     __shared__ u32 pbuf[2][64];
+    __shared__ int P_s[kMaxPlanN + 1], base_s[kMaxPlanN + 1];
 
     const int lane = threadIdx.x;
     const int r = lane / LPR, c = lane % LPR;
     // gridDim == Wh * Hkv: wave (wh, g) serves KV head g only.  Consecutive workgroups land on
     // consecutive XCDs, so with Hkv == 8 every XCD streams (and caches) the tiles of one KV head.
-    // Its records: the shared-prefix records wh, wh + Wh, ... below n1, then the private-page
-    // records n1 + [off2[wh], off2[wh + 1]).
+    // The wave works out its own run of private pages (attn_common.h) and walks its records.
     const int g = blockIdx.x % a.Hkv;
     const int wh = blockIdx.x / a.Hkv;
-    if (!plan_usable(a)) return;
-    const int n1 = a.hdr->n1;
-    const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
-    if (p2_begin < n1 || p2_end < p2_begin || p2_end > a.hdr->total) {
-        if (lane == 0) report(a.status, STEP_EPLAN);
-        return;
-    }
-    auto next_record = [&](int id) {  // id of the record after `id` in this wave's list, -1 at the end
-        int nx;
-        if (id < n1) {
-            nx = id + a.Wh;
-            if (nx >= n1) nx = p2_begin;
-        } else {
-            nx = id + 1;
-        }
-        return nx < p2_end ? nx : -1;
-    };
-    // (with attn_prefix the shared-prefix records are not this kernel's)
-    int rec_id = (wh < n1 && !a.hdr->prefix_mfma) ? wh : (p2_begin < p2_end ? p2_begin : -1);
-    if (rec_id < 0) return;
+    const WavePlan wp = plan_build(a, lane, P_s, base_s, blockIdx.x == 0);
+    if (blockIdx.x == 0) publish_plan(a, wp, lane, P_s, base_s);
+    RunWalker walk(a, wp, P_s, base_s, wh);
+    if (!walk.more()) return;
     if (a.NP <= 0) {
         if (lane == 0) report(a.status, STEP_EPAGE);
         return;
@@ -115,14 +99,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     float m_own, l_own, mx_pending;
 
     // The lanes of a row group exchange their weights through pbuf: lane l writes word l, the group's other
-    // lanes read it.  A single wave's LDS operations retire in order; these fences and the wave barrier
-    // (no instructions) also forbid the compiler to move the reads and writes across the exchange points.
-    auto wave_lds_sync = [&]() {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-
+    // lanes read it (wave_lds_sync marks the exchange points).
     auto phaseA = [&](const uint4 (&k)[IPP], int slot, int ntok) {
         float val[NV];
 #pragma unroll
@@ -206,20 +183,8 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
             if (jj * TPI + r >= ntok) v[jj] = make_uint4(0, 0, 0, 0);
     };
 
-    // a record that points outside the block tables (a workspace overwritten after planning) is
-    // replaced by a one-token record of trace 0 and reported; nothing is read out of bounds
-    bool bad_plan = false;
-    auto record_at = [&](int id) {
-        Record x = scalar_read(a.records + id);
-        const bool ok = (u32)x.i < (u32)a.N && x.first >= 0 && x.n >= 1 && (long long)x.first + x.n <= a.MAXB &&
-                        x.ntok >= 1 && x.ntok <= kPageTokens;
-        bad_plan |= !ok;
-        if (!ok) x = Record{0, 0, 1, 1};
-        return x;
-    };
-
     uint4 k0[IPP], v0[IPP], k1[IPP], v1[IPP];
-    Record rec = record_at(rec_id);
+    Record rec = walk.take();
     {
         const int32_t *bt0 = a.block_tables + (size_t)rec.i * a.MAXB + rec.first;
         const size_t t0 = tile_at(scalar_read(bt0)), t1 = tile_at(scalar_read(bt0 + (rec.n > 1 ? 1 : 0)));
@@ -231,11 +196,10 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
     }
 
     for (;;) {
-        const int next_id = next_record(rec_id);
-        const bool has_next = next_id >= 0;
+        const bool has_next = walk.more();
         // the next record and the ids of its first two pages are fetched now and consumed after this
         // record's pages
-        const Record nrec = record_at(has_next ? next_id : rec_id);
+        const Record nrec = has_next ? walk.take() : rec;
         const int32_t *nbt = a.block_tables + (size_t)nrec.i * a.MAXB + nrec.first;
         const int npage0 = scalar_read(nbt), npage1 = scalar_read(nbt + (nrec.n > 1 ? 1 : 0));
 
@@ -304,7 +268,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         lh[1] = dpp<STEP_DPP_QUAD_BCAST(1)>(ls);
         lh[2] = dpp<STEP_DPP_QUAD_BCAST(2)>(ls);
         lh[3] = dpp<STEP_DPP_QUAD_BCAST(3)>(ls);
-        const size_t slot = (size_t)rec_id * a.Hkv + g;
+        const size_t slot = (size_t)rec.slot * a.Hkv + g;
         float *pacc = a.part_acc + slot * (G * D);
         float *pml = a.part_ml + slot * (G * 2);
 #pragma unroll
@@ -336,9 +300,7 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
         }
         if (!has_next) break;
         rec = nrec;
-        rec_id = next_id;
     }
-    if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 

@@ -16,18 +16,18 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
     const int i = blockIdx.x / a.Hq, h = blockIdx.x % a.Hq;
     const int g = h / G, hh = h % G;
     uint16_t *orow = a.out + ((size_t)i * a.Hq + h) * D;
-    const int L = a.seq_lens[i];
-    // the trace's records: `parts` shared-prefix sub-chunks, then cnt2 consecutive private ones
-    const bool usable = plan_usable(a);
-    const int parts = a.hdr->parts, n_live = a.hdr->n_live;
-    const int rk = a.rank[i], f2 = a.first2[i];
-    int nch = parts + a.cnt2[i];
-    if (L <= 0 || (long long)L > (long long)a.MAXB * kPageTokens || !usable) nch = 0;
-    if (nch > 0 && ((u32)rk >= (u32)n_live || f2 < 0 || a.cnt2[i] < 0 || f2 + a.cnt2[i] > a.hdr->total)) {
+    // the trace's partials: parts_b sub-chunks of its block's shared prefix (slots p * N + i), then cnt2
+    // consecutive private-page records from first2
+    const int nb = pages_of(a.seq_lens[i], a.MAXB);
+    int parts, sc;
+    prefix_split(a, clamp_shared(a, a.blk_shared[i / a.TB], nb), parts, sc);
+    const int f2 = a.first2[i], c2 = a.cnt2[i];
+    int nch = nb > 0 ? parts + c2 : 0;
+    if (nch > 0 && (c2 < 0 || f2 < a.N * a.pmax || (long long)f2 + c2 > a.max_slots)) {
         if (lane == 0) report(a.status, STEP_EPLAN);
         nch = 0;
     }
-    auto slot_of = [&](int ch) { return (size_t)(ch < parts ? ch * n_live + rk : f2 + (ch - parts)) * a.Hkv + g; };
+    auto slot_of = [&](int ch) { return (size_t)(ch < parts ? ch * a.N + i : f2 + (ch - parts)) * a.Hkv + g; };
 
     float o[DPT];
 #pragma unroll

@@ -1,5 +1,6 @@
-// The matrix-core kernels of paged_decode_attn: attn_prefix (pages shared by every live trace) and
-// attn_partial_mfma (stage 1 over private pages for every shape but G = 4, D = 128).
+// The matrix-core kernels of paged_decode_attn: attn_front (the pages shared by the live traces of a block
+// of traces, and the per-block shared-prefix lengths the rest of the call is cut by) and attn_partial_mfma
+// (stage 1 over private pages for every shape but G = 4, D = 128).
 #include "attn_common.h"
 
 namespace step {
@@ -133,71 +134,77 @@ struct MfmaPair {
 };
 
 // ---------------------------------------------------------------------------------------------
-// shared prefix on the matrix cores.  The S leading pages are the same physical pages for every live
-// trace, so for one KV head the n_live * G query rows that attend to them form a dense matrix: the
-// logits are K Q^T and the output V^T P^T, both v_mfma_f32_16x16x32_bf16, and every shared tile is
-// read once per block of query rows instead of once per trace.  One wave per (KV head, block of
-// 16 * QT query rows, sub-chunk p of the prefix); it writes the partial (m, l, acc) of the shared-prefix
-// records p * n_live + rank, exactly what stage 1 would have written for them, so the merge does
-// not change.
-//
+// attn_front: shared prefixes on the matrix cores, one wave per (KV head g, block b of TB traces, sub-chunk p).
+// The S_b leading pages of block b are the same physical pages for every live trace of the block, so for
+// one KV head the TB * G query rows that attend to them form a dense 16 * QT-row matrix: the logits are
+// K Q^T and the output V^T P^T, both v_mfma_f32_16x16x32_bf16, and every shared tile is read once per block
+// instead of once per trace.  The wave finds S_b itself from the block's block-table rows (DETECT; every
+// unit of a block computes the same value, unit (0, b, 0) stores it for the streaming kernel and the merge),
+// or takes it from the workspace (a plan made earlier by step_attn_plan), works out the sub-chunks
+// (prefix_split) and, if p is one of them, writes the partial (m, l, acc) of slot p * N + t for every live
+// trace t of the block -- exactly what a streaming wave writes for a record, so the merge treats both alike.
 // (operand layouts: MfmaPair above)
-// These units are a launch of their own, ahead of stage 1.  Run inside the stage-1 launch, next to
-// the streaming waves (both fit on a SIMD), they were measured to cost more than they do alone: every
-// streaming wave owns the same share of pages, so the wave that shares its SIMD longest sets the
-// kernel's end.
-template <int D, int QT>
-__global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
+// ---------------------------------------------------------------------------------------------
+template <int D, int QT, bool DETECT>
+__global__ __launch_bounds__(64) void attn_front(const AttnArgs a)
 {
     typedef MfmaPair<D> MP;
     constexpr int KB = MP::KB, DB = MP::DB;
     typedef typename MP::VRow VRow;
     const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
-    if (!plan_usable(a)) return;
-    const PlanHeader *hd = a.hdr;
-    if (!hd->prefix_mfma) return;
-    const int S = hd->shared, parts = hd->parts, n_live = hd->n_live, sc = hd->part_pages;
     const int G = a.Hq / a.Hkv;
-    const int rows = n_live * G;
-    const int nqb = (a.N * G + 16 * QT - 1) / (16 * QT);
     int u = blockIdx.x;
     const int g = u % a.Hkv;
     u /= a.Hkv;
-    const int qb = u % nqb, p = u / nqb;
-    if (p >= parts || qb * 16 * QT >= rows) return;
+    const int b = u % a.nblk, p = u / a.nblk;
+    const int t0 = b * a.TB;
+
+    int minfull;
+    const unsigned live = block_live(a, b, lane, minfull);
+    int S;
+    if constexpr (DETECT) {
+        S = block_shared_pages(a, b, lane, live, minfull);
+        if (p == 0 && g == 0 && lane == 0) {
+            a.blk_shared[b] = S;
+            if (b == 0) a.hdr->stamp = a.stamp;
+        }
+    } else {
+        // lengths made for other dims (or none at all) are reported; the clamp keeps every access inside
+        // the block tables whatever the workspace holds
+        if (a.hdr->stamp != a.stamp && lane == 0) report(a.status, STEP_EPLAN);
+        S = __popc(live) >= 2 ? min(max(scalar_read(a.blk_shared + b), 0), min(min(kMaxShared, minfull), a.MAXB)) : 0;
+    }
+    int parts, sc;
+    prefix_split(a, S, parts, sc);
+    if (p >= parts) return;
     const int first = p * sc, n = min(sc, S - first);
-    if (n < 1 || S > kMaxShared || a.NP <= 0) {
-        if (lane == 0) report(a.status, a.NP <= 0 ? STEP_EPAGE : STEP_EPLAN);
+    if (n < 1) return;
+    if (a.NP <= 0) {
+        if (lane == 0) report(a.status, STEP_EPAGE);
         return;
     }
 
-    bool bad_plan = false, bad_page = false;
-    auto trace_of_rank = [&](int rk) {
-        const int t = a.live[rk];
-        const bool ok = (u32)t < (u32)a.N;
-        bad_plan |= !ok;
-        return ok ? t : 0;
-    };
-    const int32_t *bt = a.shared_pages + first;  // first + n <= S <= kMaxShared
+    bool bad_page = false;
+    const int32_t *bt = a.block_tables + (size_t)(t0 + __ffs(live) - 1) * a.MAXB + first;  // first + n <= S <= MAXB
     auto page_at = [&](int j) {
-        const int pg = scalar_read(bt + min(j, n - 1));  // written by attn_plan, the same for every lane
+        const int pg = scalar_read(bt + min(j, n - 1));  // the same for every lane
         const bool ok = (u32)pg < (u32)a.NP;
         bad_page |= !ok;
         return ok ? pg : 0;
     };
 
-    // query rows of this block: row = rank * G + head-in-group
+    // query rows of this block: row = (trace - t0) * G + head-in-group
     uint4 qf[QT][KB];
-    int rank_of[QT], hh_of[QT];
+    int trace_of[QT], hh_of[QT];
     bool valid[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        const int row = (qb * QT + qt) * 16 + c;
-        valid[qt] = row < rows;
-        const int rw = valid[qt] ? row : 0;
-        rank_of[qt] = rw / G;
-        hh_of[qt] = rw % G;
-        const uint16_t *qrow = a.q + ((size_t)trace_of_rank(rank_of[qt]) * a.Hq + g * G + hh_of[qt]) * D;
+        const int row = qt * 16 + c;
+        const int r = row / G;
+        valid[qt] = r < a.TB && ((live >> r) & 1u);
+        trace_of[qt] = valid[qt] ? t0 + r : t0 + __ffs(live) - 1;
+        hh_of[qt] = row % G;
+        const uint16_t *qrow = a.q + ((size_t)trace_of[qt] * a.Hq + g * G + hh_of[qt]) * D;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const uint4 x = *reinterpret_cast<const uint4 *>(qrow + kb * 32 + gr * 8);
@@ -249,45 +256,58 @@ __global__ __launch_bounds__(64) void attn_prefix(const AttnArgs a)
     constexpr int NBUF = QT == 1 ? 3 : 2;
     uint4 kf[NBUF][2][KB];
     VRow vr[NBUF][8];
-    // the units that share this sub-chunk (same KV head, other query blocks) walk its pairs in
-    // rotated orders, so that they do not all ask the L2 for the same lines at the same moment
+    // the units that share this sub-chunk (same KV head, other blocks with the same prompt) walk its pairs
+    // in rotated orders, so that they do not all ask the L2 for the same lines at the same moment
     const int np = (n + 1) / 2;
-    const int rot = qb % np;
+    const int rot = b % np;
     auto pair_at = [&](int t) { return 2 * ((t + rot) % np); };  // first page of the t-th pair visited
 #pragma unroll
-    for (int b = 0; b < NBUF; ++b)
-        if (b < np) load_pair(pair_at(b), kf[b], vr[b]);
-    for (int t0 = 0; t0 < np; t0 += NBUF) {
+    for (int bf = 0; bf < NBUF; ++bf)
+        if (bf < np) load_pair(pair_at(bf), kf[bf], vr[bf]);
+    for (int i0 = 0; i0 < np; i0 += NBUF) {
 #pragma unroll
-        for (int b = 0; b < NBUF; ++b) {
-            const int t = t0 + b;
+        for (int bf = 0; bf < NBUF; ++bf) {
+            const int t = i0 + bf;
             if (t < np) {
-                // an odd sub-chunk ends on half a pair: that pair's second page gets no weight
-                attend_pair(kf[b], vr[b], pair_at(t) + 1 < n);
-                if (t + NBUF < np) load_pair(pair_at(t + NBUF), kf[b], vr[b]);
+                attend_pair(kf[bf], vr[bf], pair_at(t) + 1 < n);
+                if (t + NBUF < np) load_pair(pair_at(t + NBUF), kf[bf], vr[bf]);
             }
         }
     }
 
-    // partials of the records p * n_live + rank
+    // partials of the slots p * N + trace
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt)
-        MP::store_partial(a, ((size_t)p * n_live + rank_of[qt]) * a.Hkv + g, G, hh_of[qt], gr, valid[qt], m[qt], l[qt], o[qt]);
-    if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
+        MP::store_partial(a, ((size_t)p * a.N + trace_of[qt]) * a.Hkv + g, G, hh_of[qt], gr, valid[qt], m[qt], l[qt], o[qt]);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
+}
+
+// step_attn_plan: the per-block shared-prefix lengths alone (one wave per block), for a decode step whose
+// layers all see the same block tables; also reports lengths outside the block-table row.
+__global__ __launch_bounds__(64) void attn_plan_blocks(const AttnArgs a)
+{
+    const int lane = threadIdx.x, b = blockIdx.x;
+    const int t0 = b * a.TB, nt = min(a.TB, a.N - t0);
+    int minfull;
+    const unsigned live = block_live(a, b, lane, minfull);
+    const int L = lane < nt ? a.seq_lens[t0 + lane] : 0;
+    if (__any(L != 0 && pages_of(L, a.MAXB) == 0) && lane == 0) report(a.status, STEP_ELEN);
+    const int S = a.prefix_qt ? block_shared_pages(a, b, lane, live, minfull) : 0;
+    if (lane == 0) {
+        a.blk_shared[b] = S;
+        if (b == 0) a.hdr->stamp = a.stamp;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // stage 1 on the matrix cores, any group size: the persistent streaming kernel for G != 4.
-// The same two products as attn_prefix with the G query heads of ONE trace in the columns (the other
+// The same two products as attn_front with the G query heads of ONE trace in the columns (the other
 // 16 - G columns are zero and never stored), over the private pages of the wave's records, pair of
 // pages by pair of pages.  The operand loads (K: 16 rows x 64 bytes per instruction, V: 4 rows x
-// 256 bytes) stream a fragmented pool as fast as the 1 KB-per-instruction loads of the G == 4 kernel
-// (measured on a bare read probe: 6.79 against 6.81 TB/s), and the arithmetic per byte no longer grows
-// with G.  Page ids, records and tiles are requested ahead of their use across record boundaries:
-// the wave's page pairs form one sequence, a load cursor runs kBufs pairs ahead of the compute cursor.
-// (The compiler parks the second buffer in accumulator registers, which makes it wait for those loads
-// early; more buffers, or refills that always issue the same number of loads, measured no faster.)
+// 256 bytes) stream a fragmented pool as fast as the 1 KB-per-instruction loads of the G == 4 kernel,
+// and the arithmetic per byte no longer grows with G.  Page ids, records and tiles are requested ahead of
+// their use across record boundaries: the wave's page pairs form one sequence, a load cursor runs kBufs
+// pairs ahead of the compute cursor.
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
@@ -297,63 +317,42 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
     constexpr int kBufs = 2;
     typedef typename MP::VRow VRow;
     typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+    __shared__ int P_s[kMaxPlanN + 1], base_s[kMaxPlanN + 1];
     const int lane = threadIdx.x, c = lane & 15, gr = lane >> 4;
     const int g = blockIdx.x % a.Hkv;
     const int wh = blockIdx.x / a.Hkv;
-    if (!plan_usable(a)) return;
     const int G = a.Hq / a.Hkv;
-    const int n1 = a.hdr->n1;
-    const int p2_begin = n1 + a.off2[wh], p2_end = n1 + a.off2[wh + 1];
-    if (p2_begin < n1 || p2_end < p2_begin || p2_end > a.hdr->total) {
-        if (lane == 0) report(a.status, STEP_EPLAN);
-        return;
-    }
-    auto next_record = [&](int id) {  // id of the record after `id` in this wave's list, -1 at the end
-        int nx;
-        if (id < n1) {
-            nx = id + a.Wh;
-            if (nx >= n1) nx = p2_begin;
-        } else {
-            nx = id + 1;
-        }
-        return nx < p2_end ? nx : -1;
-    };
-    const int first_id = (wh < n1 && !a.hdr->prefix_mfma) ? wh : (p2_begin < p2_end ? p2_begin : -1);
-    if (first_id < 0) return;
+    const WavePlan wp = plan_build(a, lane, P_s, base_s, blockIdx.x == 0);
+    if (blockIdx.x == 0) publish_plan(a, wp, lane, P_s, base_s);
+    RunWalker walk(a, wp, P_s, base_s, wh);
+    if (!walk.more()) return;
     if (a.NP <= 0) {
         if (lane == 0) report(a.status, STEP_EPAGE);
         return;
     }
 
-    bool bad_plan = false, bad_page = false;
-    auto record_at = [&](int id) {  // a record that points outside the block tables is replaced and reported
-        Record x = scalar_read(a.records + id);
-        const bool ok = (u32)x.i < (u32)a.N && x.first >= 0 && x.n >= 1 && (long long)x.first + x.n <= a.MAXB &&
-                        x.ntok >= 1 && x.ntok <= kPageTokens;
-        bad_plan |= !ok;
-        if (!ok) x = Record{0, 0, 1, 1};
-        return x;
-    };
-
-    // a position in the wave's sequence of page pairs: pages j and j + 1 of record id
+    bool bad_page = false;
+    // a position in the wave's sequence of page pairs: pages j and j + 1 of record rec
     struct Cursor {
-        int id;      // < 0: past the end
-        int next_id; // the record after it
-        Record rec, next_rec;
+        bool valid;
+        Record rec;
         int j;
     };
-    auto enter = [&](int id, const Record &rec) {  // first pair of record id; its successor is fetched now, used later
+    auto next_record = [&]() {
         Cursor x;
-        x.id = id;
-        x.rec = rec;
+        x.valid = walk.more();
         x.j = 0;
-        x.next_id = id >= 0 ? next_record(id) : -1;
-        x.next_rec = x.next_id >= 0 ? record_at(x.next_id) : Record{0, 0, 1, 1};
+        x.rec = x.valid ? walk.take() : Record{0, 0, 1, 1, 0};
         return x;
     };
-    auto advance = [&](Cursor &x) {
-        x.j += 2;
-        if (x.j >= x.rec.n) x = enter(x.next_id, x.next_rec);
+    Cursor cur = next_record();   // load cursor
+    Cursor after = next_record(); // the record after the load cursor's, worked out one record early
+    auto advance = [&]() {
+        cur.j += 2;
+        if (cur.j >= cur.rec.n) {
+            cur = after;
+            if (cur.valid) after = next_record();
+        }
     };
     auto page_ids = [&](const Cursor &x, int &p0, int &p1) {  // second page of an odd record's last pair: the last page again
         const int32_t *row = a.block_tables + (size_t)x.rec.i * a.MAXB + x.rec.first;
@@ -414,27 +413,26 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
     uint4 qslot[kBufs][KB];
     Cursor at[kBufs];
 
-    Cursor cur = enter(first_id, record_at(first_id));  // load cursor
-    int id0, id1;                                       // page ids of the load cursor's pair
+    int id0, id1;  // page ids of the load cursor's pair
     page_ids(cur, id0, id1);
     auto fill = [&](uint4 (&kfb)[2][KB], VRow (&vrb)[8], uint4 (&qb)[KB], Cursor &slot) {
         slot = cur;
-        if (cur.id < 0) return;
+        if (!cur.valid) return;
         load_pair(id0, id1, kfb, vrb);
         if (cur.j == 0) load_q(cur.rec.i, qb);
-        advance(cur);
-        if (cur.id >= 0) page_ids(cur, id0, id1);  // scalar loads, used one refill later
+        advance();
+        if (cur.valid) page_ids(cur, id0, id1);  // scalar loads, used one refill later
     };
 #pragma unroll
-    for (int b = 0; b < kBufs; ++b) fill(kf[b], vr[b], qslot[b], at[b]);
+    for (int bf = 0; bf < kBufs; ++bf) fill(kf[bf], vr[bf], qslot[bf], at[bf]);
 
     bool done = false;
     while (!done) {
 #pragma unroll
-        for (int b = 0; b < kBufs; ++b) {
+        for (int bf = 0; bf < kBufs; ++bf) {
             if (done) continue;
-            const Cursor x = at[b];
-            if (x.id < 0) {
+            const Cursor x = at[bf];
+            if (!x.valid) {
                 done = true;
                 continue;
             }
@@ -444,35 +442,43 @@ __global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
 #pragma unroll
                 for (int jt = 0; jt < DB; ++jt) o[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) qf[kb] = qslot[b][kb];
+                for (int kb = 0; kb < KB; ++kb) qf[kb] = qslot[bf][kb];
             }
             const int n = x.rec.n;
             auto tokens_of = [&](int jj) { return jj < n - 1 ? kPageTokens : (jj == n - 1 ? x.rec.ntok : 0); };
-            attend_pair(kf[b], vr[b], tokens_of(x.j), tokens_of(x.j + 1));
+            attend_pair(kf[bf], vr[bf], tokens_of(x.j), tokens_of(x.j + 1));
             const bool last = x.j + 2 >= n;
-            fill(kf[b], vr[b], qslot[b], at[b]);  // the buffer is free: request the pair kBufs ahead
-            if (last) MP::store_partial(a, (size_t)x.id * a.Hkv + g, G, min(c, G - 1), gr, c < G, m, l, o);
+            fill(kf[bf], vr[bf], qslot[bf], at[bf]);  // the buffer is free: request the pair kBufs ahead
+            if (last) MP::store_partial(a, (size_t)x.rec.slot * a.Hkv + g, G, min(c, G - 1), gr, c < G, m, l, o);
         }
     }
-    if (bad_plan && lane == 0) report(a.status, STEP_EPLAN);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 
 }  // namespace
 
-void launch_prefix(const AttnArgs &a, int D, hipStream_t s)
+void launch_front(const AttnArgs &a, int D, bool detect, hipStream_t s)
 {
     if (!a.prefix_qt) return;
-    const int G = a.Hq / a.Hkv;
-    const int nqb = (a.N * G + 16 * a.prefix_qt - 1) / (16 * a.prefix_qt);
-    const dim3 grid((u32)(a.Hkv * nqb * kMaxParts));  // units beyond the plan's sub-chunks and rows exit at once
+    const dim3 grid((u32)(a.Hkv * a.nblk * a.pmax));  // units beyond a block's sub-chunks exit once they know S_b
+#define STEP_FRONT(DD, QQ)                                                                     \
+    do {                                                                                       \
+        if (detect) hipLaunchKernelGGL((attn_front<DD, QQ, true>), grid, dim3(64), 0, s, a);   \
+        else hipLaunchKernelGGL((attn_front<DD, QQ, false>), grid, dim3(64), 0, s, a);         \
+    } while (0)
     if (D == 128) {
-        if (a.prefix_qt == 2) hipLaunchKernelGGL((attn_prefix<128, 2>), grid, dim3(64), 0, s, a);
-        else hipLaunchKernelGGL((attn_prefix<128, 1>), grid, dim3(64), 0, s, a);
+        if (a.prefix_qt == 2) STEP_FRONT(128, 2);
+        else STEP_FRONT(128, 1);
     } else {
-        if (a.prefix_qt == 2) hipLaunchKernelGGL((attn_prefix<64, 2>), grid, dim3(64), 0, s, a);
-        else hipLaunchKernelGGL((attn_prefix<64, 1>), grid, dim3(64), 0, s, a);
+        if (a.prefix_qt == 2) STEP_FRONT(64, 2);
+        else STEP_FRONT(64, 1);
     }
+#undef STEP_FRONT
+}
+
+void launch_plan_blocks(const AttnArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(attn_plan_blocks, dim3((u32)a.nblk), dim3(64), 0, s, a);
 }
 
 void launch_stream_mfma(const AttnArgs &a, int D, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
