@@ -10,11 +10,15 @@ of the single lowest-scoring trace).  Inputs are resident in HBM before the time
 Every step gets its own copy of the (small) mutable state so that pruning does not shrink the
 next step's work.
 
-Prints ONE JSON line: metric, value, unit, ms_per_step, config, plus "roofline" (the dominant
-kernel against the HBM peak) and "cpu_baseline" (the oracle on the host cores).  The roofline is
-measured live with HIP events around the stage-1 attention kernel of every timed step.
+Prints ONE JSON line: metric, value, unit, ms_per_step, config, plus
+  "roofline"        the dominant kernel (attention stage 1) against the HBM peak, from HIP events attached
+                    to that kernel's launches, live in this run;
+  "attention"       the whole paged_decode_attn call (all its kernels, all its bytes) against the same peak;
+  "step_breakdown"  microseconds per step of every kernel of the step (same events);
+  "cpu_baseline"    the oracle on the host cores.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -35,6 +39,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5], help="workload config, 1-based (3: the N = 64 headline)")
     ap.add_argument("--layers", type=int, default=None, help="layers per step (default: the config's; config 4: 36)")
     ap.add_argument("--prune-k", type=int, default=None, help="traces pruned per step (default 1; config 5: 64)")
+    ap.add_argument("--heads", default=None, metavar="HQ/HKV", help="another head shape on the config's lengths, e.g. 32/4")
+    ap.add_argument("--head-dim", type=int, default=None, choices=[64, 128], help="another head dimension on the config's lengths")
+    ap.add_argument("--scorer", default=None, metavar="D,M,B", help="another scorer shape, e.g. 4096,512,26 (the paper's width is 512)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["step", "loop"], default="step",
@@ -46,19 +53,41 @@ def parse_args():
     ap.add_argument("--graph", action="store_true", help="record the K timed steps as one HIP graph and time its replay")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="only run libstep's plain copy kernel on MIB MiB (profiler byte-counter calibration)")
+    ap.add_argument("--read-probe", action="store_true",
+                    help="only run the bare tile-read probe on the config's pool and private pages (what HBM delivers "
+                         "to the streaming kernel's access pattern with no arithmetic behind it)")
     return ap.parse_args()
 
 
+def kernel_source_hash():
+    """sha256 over the HIP sources: a committed counter summary is quoted only for the code it was measured on."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2601_09093_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def traffic_from_profiles(kernel, workload):
-    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary for it is committed."""
-    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    """(bytes per launch, source note): HBM bytes measured with rocprofv3 --pmc, taken from the committed summary
+    only if that summary was made from the kernel sources of this tree; otherwise (None, why)."""
+    rel = os.path.join("profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    val = sha = None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                val = float(line.split(":", 1)[1])
+            if line.startswith("source_sha256:"):
+                sha = line.split(":", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no counter summary for this workload under profiles/"
+    if val is None:
+        return None, "%s holds no traffic figure" % rel
+    if sha != kernel_source_hash():
+        return None, "%s was measured on other kernel sources (%s): not quoted" % (rel, sha)
+    return val, "%s (two rocprofv3 --pmc runs of this command on these kernel sources, %s)" % (rel, sha)
 
 
 def main():
@@ -94,8 +123,12 @@ def main():
         return
 
     K, W = args.steps, args.warmup
-    w = wl.make_workload(args.config, kv=False)
+    heads = tuple(int(x) for x in args.heads.split("/")) if args.heads else None
+    w = wl.make_workload(args.config, kv=False, heads=heads, head_dim=args.head_dim)
     lay, s, sc = w.layout, w.shape, w.scorer
+    if args.scorer:
+        d_, m_, B_ = (int(x) for x in args.scorer.split(","))
+        sc = wl.build_scorer(w.seed, s.N, s.N, d_, m_, B_, 0, prior_state=(args.config == 5))
     prune_k = args.prune_k if args.prune_k is not None else (w.prune_k if args.config == 5 else 1)
 
     def bits(a):
@@ -128,6 +161,16 @@ def main():
         k_layers.append(pair[0])
         v_layers.append(pair[1])
     k_pages, v_pages = k_layers[0], v_layers[0]
+    G = s.Hq // s.Hkv
+    nb = (lay.seq_lens.astype(np.int64) + s.P - 1) // s.P
+    workload = "config%d" % args.config + ("-loop" if args.mode == "loop" else "")
+    if heads or args.head_dim:
+        workload += "-%dq%dkv-d%d" % (s.Hq, s.Hkv, s.D)
+
+    if args.read_probe:
+        read_probe(args, binding, torch, np, w, k_pages, v_pages, workload)
+        return
+
     q = bits(w.q)
     out = torch.empty_like(q)
     q_layers = [q] + [torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
@@ -164,7 +207,7 @@ def main():
     def step(i):
         if layers == 1:
             binding.paged_decode_attn(q, k_pages, v_pages, bt_s[i], sl_s[i], out=out, workspace=ws_attn, status=status)
-        else:  # one plan per step, shared by every layer's attention
+        else:  # the per-block shared-prefix lengths are found once per step and shared by every layer's attention
             binding.attn_plan(q, k_pages, bt_s[i], sl_s[i], ws_attn, status=status)
             for l in range(layers):
                 binding.paged_decode_attn_planned(q_layers[l], k_layers[l], v_layers[l], bt_s[i], sl_s[i], out,
@@ -191,6 +234,8 @@ def main():
         new_pages_l = torch.empty(s.N, dtype=torch.int32, device=dev)
         ws_res = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(s.N, bt_np.shape[1], lay.NP)), dev)
         live_at_start = int((lay.seq_lens > 0).sum())
+        adims = binding.attn_dims(q, k_pages, bt_l)
+        ws_attn = binding.new_workspace(binding.attn_workspace_bytes(adims), dev)
 
         def step(i):  # noqa: F811  (replaces the per-copy step above)
             binding.reserve_pages(scores, rc_l, bt_l, sl_l, pruned=pruned_l, n_pruned=n_pruned_l,
@@ -202,7 +247,7 @@ def main():
                                workspace=ws_score, status=status)
         n_freed.fill_(1)
 
-    # state copies: W warm-up steps, K timed steps, K more steps with stage 1 bracketed by events
+    # state copies: W warm-up steps, K timed steps, K more steps with every kernel bracketed by events
     for i in range(W):
         step(i)
     graph = None
@@ -223,44 +268,67 @@ def main():
             step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    # the same K steps again with HIP events around the stage-1 attention kernel of every step (the
-    # event records cost a few microseconds each, so they stay out of the step time above)
-    binding.attn_profile_begin(K * layers)
+    # the same K steps again with HIP events attached to every kernel launch (the event records cost a few
+    # microseconds each, so they stay out of the step time above)
+    cap = K * (3 * layers + 12)
+    binding.profile_begin(cap)
     for i in range(W + K, W + 2 * K):
         step(i)
     torch.cuda.synchronize()
-    stage1_ms = binding.attn_profile_end(K * layers)
+    timed = binding.profile_end(cap)
     assert int(status.item()) == 0, binding.ERROR_NAMES.get(int(status.item()))
     assert int(n_freed.item()) > 0 or prune_k == 0
+    per_kernel = {}
+    for name, ms in timed:
+        per_kernel.setdefault(name, []).append(ms)
+    stage1_ms = per_kernel["attn_partial"]
+    assert len(stage1_ms) == K * layers
+    breakdown = {name: round(1e3 * float(np.sum(v)) / K, 2) for name, v in per_kernel.items()}   # us per step
+    launches_per_step = len(timed) / K
 
     ms_per_step = (t1 - t0) * 1e3 / K
     value = s.N / (ms_per_step * 1e-3)                              # trace-tokens per second
 
     # ---- roofline of the dominant kernel (attention stage 1) --------------------------------
-    nb = (lay.seq_lens.astype(np.int64) + s.P - 1) // s.P
-    G = s.Hq // s.Hkv
     hdr = ws_attn[:64].view(torch.int32).cpu().tolist()              # figures of the cut left by the streaming kernel
     pieces, private_pages, quota, prefix_slots, shared_pages = hdr[1], hdr[2], hdr[3], hdr[4], hdr[5]
-    n_live = int((lay.seq_lens > 0).sum())
-    assert private_pages == int(nb.sum()) - n_live * shared_pages, "per-block shared prefixes differ: not this workload"
+    lens_now = sl_l.cpu().numpy() if args.mode == "loop" else lay.seq_lens
+    nb_now = (lens_now.astype(np.int64) + s.P - 1) // s.P
+    n_live = int((lens_now > 0).sum())
+    assert private_pages == int(nb_now.sum()) - n_live * shared_pages, "per-block shared prefixes differ: not this workload"
     # the shared prompt runs on the matrix cores (attn_front); stage 1 streams the private pages only
-    stage1_tokens = lay.requested_tokens - n_live * shared_pages * s.P
+    stage1_tokens = int(lens_now.sum()) - n_live * shared_pages * s.P
+    part_bytes = s.Hkv * G * (s.D + 2) * 4                          # one partial slot: (m, l, acc) of every query head
     alg_bytes = (stage1_tokens * s.kv_bytes_per_token               # every KV byte stage 1 is responsible for, once
                  + private_pages * 4                                # block-table entries
                  + s.N * s.Hq * s.D * 2                             # q
-                 + pieces * s.Hkv * G * (s.D + 2) * 4)              # split-K partials written by stage 1
+                 + pieces * part_bytes)                             # split-K partials written by stage 1
     # the "requested" variant counts every trace's own view of its context (the shared prompt N times)
-    req_bytes = alg_bytes + (lay.requested_tokens - lay.unique_tokens) * s.kv_bytes_per_token
+    req_bytes = alg_bytes + n_live * shared_pages * s.P * s.kv_bytes_per_token
     avg_ms = float(np.mean(stage1_ms))
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
-    workload = "config%d" % args.config + ("-loop" if args.mode == "loop" else "")
+    traffic, traffic_source = traffic_from_profiles("attn_partial", workload)
     roofline = {
         "kernel": "attn_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": traffic_from_profiles("attn_partial", "config%d" % args.config),
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
         "algorithmic_bytes": int(alg_bytes), "requested_bytes": int(req_bytes), "avg_kernel_ms": round(avg_ms, 4),
         "median_kernel_ms": round(float(np.median(stage1_ms)), 4),
         "min_kernel_ms": round(float(np.min(stage1_ms)), 4), "launches": len(stage1_ms),
+    }
+    # ---- the whole attention call: every byte it has to move, every kernel it launches --------
+    unique_tokens = stage1_tokens + (shared_pages * s.P if n_live else 0)
+    attn_bytes = (unique_tokens * s.kv_bytes_per_token               # every resident referenced K/V byte once
+                  + int(nb_now.sum()) * 4                            # block-table entries
+                  + 2 * s.N * s.Hq * s.D * 2                         # q in, out
+                  + 2 * (pieces + prefix_slots) * part_bytes)        # partials written, then read by the merge
+    attn_us = sum(breakdown.get(kname, 0.0) for kname in ("attn_front", "attn_plan_blocks", "attn_partial", "attn_merge")) / layers
+    attn_gbs = attn_bytes / (attn_us * 1e-6) / 1e9
+    attention = {
+        "bytes": int(attn_bytes), "us": round(attn_us, 2), "achieved": round(attn_gbs, 1), "unit": "GB/s",
+        "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
+        "whole_step_frac": round(attn_bytes * layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "note": "all kernels of one paged_decode_attn call (per layer) over all its bytes; whole_step_frac divides the "
+                "same bytes by ms_per_step (scorer and pruning included in the time)",
     }
 
     result = {
@@ -274,9 +342,11 @@ def main():
                        sc.hidden.shape[1], sc.W1.shape[0], "ReLU" if sc.act == 0 else "GELU", B),
                    "prune_k": prune_k, "attn_waves_per_kv_head": binding.attn_waves_per_head(adims),
                    "attn_records": pieces, "attn_pages_per_wave": quota, "shared_prefix_pages_on_mfma": shared_pages,
-                   "mode": args.mode, "launch": "hip-graph" if args.graph else "stream"},
-        "attn_hbm_gbs": round(achieved, 1), "attn_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
-        "roofline": roofline,
+                   "mode": args.mode, "launch": "hip-graph" if args.graph else "stream",
+                   "kernel_launches_per_step": round(launches_per_step, 2)},
+        "stage1_hbm_gbs": round(achieved, 1), "stage1_pct_of_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+        "attn_hbm_gbs": round(attn_gbs, 1), "attn_pct_of_peak": round(100 * attn_gbs / HBM_PEAK_GBS, 2),
+        "roofline": roofline, "attention": attention, "step_breakdown": breakdown,
     }
 
     if args.mode == "loop":
@@ -285,59 +355,101 @@ def main():
         result["config"]["live_traces_at_end"] = int((sl_l > 0).sum().item())
         result["config"]["free_pages_at_start"] = args.free_pages
     if not args.no_cpu_baseline and args.mode == "step":
-        result["cpu_baseline"] = cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k, layers)
+        result["cpu_baseline"] = cpu_baseline(args, w, sc, k_layers, v_layers, q_layers, sum0, cnt0, prune_k, layers)
     print(json.dumps(result))
 
 
-def cpu_baseline(args, w, k_pages, v_pages, sum0, cnt0, prune_k, layers=1):
+def read_probe(args, binding, torch, np, w, k_pages, v_pages, workload):
+    """Bare tile reads over the workload's pool: what the memory system delivers with no arithmetic behind it."""
+    lay, s = w.layout, w.shape
+    if s.D != 128:
+        print("bench.py --read-probe: 4096-byte tiles (head_dim 128) only", file=sys.stderr)
+        sys.exit(2)
+    dev = k_pages.device
+    pp = lay.prompt_len // s.P
+    nb = (lay.seq_lens.astype(np.int64) + s.P - 1) // s.P
+    private = np.concatenate([lay.block_tables[i, pp:nb[i]] for i in range(s.N) if nb[i] > pp]).astype(np.int32)
+    adims = binding.AttnDims(s.N, s.Hq, s.Hkv, s.D, s.P, lay.MAXB, lay.NP, 1.0)
+    waves = binding.attn_waves_per_head(adims)
+    ppw = (private.size // waves) & ~1
+    orders = {"random (the workload's private pages in trace order)": private[: waves * ppw],
+              "sequential (the same number of pages, ascending ids)": np.arange(waves * ppw, dtype=np.int32) % lay.NP}
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    rows = []
+    for oname, ids in orders.items():
+        ids_d = torch.from_numpy(np.ascontiguousarray(ids)).to(dev)
+        for pattern, pname in ((0, "1 KB per load"), (1, "matrix-core operand pattern")):
+            for nt in (0, 1):
+                for _ in range(3):
+                    binding.read_probe(k_pages, v_pages, ids_d, waves, ppw, pattern, nt, sink)
+                binding.profile_begin(args.steps)
+                for _ in range(args.steps):
+                    binding.read_probe(k_pages, v_pages, ids_d, waves, ppw, pattern, nt, sink)
+                torch.cuda.synchronize()
+                ms = [m for _, m in binding.profile_end(args.steps)]
+                nbytes = waves * ppw * s.Hkv * 8192
+                rows.append({"order": oname, "loads": pname, "nontemporal": bool(nt), "bytes": nbytes,
+                             "avg_ms": round(float(np.mean(ms)), 4), "min_ms": round(float(np.min(ms)), 4),
+                             "GB/s": round(nbytes / (float(np.mean(ms)) * 1e-3) / 1e9, 1)})
+    print(json.dumps({"read_probe": workload, "waves_per_kv_head": waves, "pages_per_wave": ppw, "launches": args.steps,
+                      "peak_GB/s": HBM_PEAK_GBS, "rows": rows}))
+
+
+def cpu_baseline(args, w, sc, k_layers, v_layers, q_layers, sum0, cnt0, prune_k, layers=1):
     """The oracle, as it stands, on the host cores: the whole step on a bounded sample of traces."""
     import numpy as np
     import torch
 
     import oracle
-    from paper_2601_09093_amd import workloads as wl
 
-    lay, s, sc = w.layout, w.shape, w.scorer
+    lay, s = w.layout, w.shape
     P = s.P
     threads = oracle.num_threads()
 
-    def sample_inputs(traces):
+    def sample_inputs(traces, layer):
         pages = np.unique(np.concatenate([lay.block_tables[t][: (lay.seq_lens[t] + P - 1) // P] for t in traces]))
         remap = -np.ones(lay.NP, np.int64)
         remap[pages] = np.arange(pages.size)
-        idx = torch.from_numpy(pages).to(k_pages.device)
-        ks = k_pages.index_select(0, idx).view(torch.int16).cpu().numpy().view(np.uint16)
-        vs = v_pages.index_select(0, idx).view(torch.int16).cpu().numpy().view(np.uint16)
+        idx = torch.from_numpy(pages).to(k_layers[layer].device)
+        ks = k_layers[layer].index_select(0, idx).view(torch.int16).cpu().numpy().view(np.uint16)
+        vs = v_layers[layer].index_select(0, idx).view(torch.int16).cpu().numpy().view(np.uint16)
         bt = np.where(lay.block_tables[traces] >= 0, remap[np.maximum(lay.block_tables[traces], 0)], -1).astype(np.int32)
-        return np.ascontiguousarray(w.q[traces]), ks, vs, bt, lay.seq_lens[traces].copy()
+        qh = q_layers[layer].view(torch.int16).cpu().numpy().view(np.uint16)
+        return np.ascontiguousarray(qh[traces]), ks, vs, bt, lay.seq_lens[traces].copy()
 
+    # several layers (config 4): the oracle is timed on the first, the middle and the last layer and the sum is
+    # scaled to all of them
+    timed_layers = [0] if layers == 1 else sorted({0, layers // 2 - (1 if layers % 2 == 0 else 0), layers - 1})
     order = np.argsort(-lay.seq_lens.astype(np.int64))             # a length-stratified sample
     probe = np.sort(order[[len(order) // 2]])
-    qs, ks, vs, bt, sl = sample_inputs(probe)
+    qs, ks, vs, bt, sl = sample_inputs(probe, 0)
     t0 = time.perf_counter()
     oracle.paged_decode_attn(qs, ks, vs, bt, sl)
     per_token = (time.perf_counter() - t0) / float(sl.sum())
-    budget_tokens = args.cpu_seconds / per_token
+    budget_tokens = args.cpu_seconds / per_token / len(timed_layers)
     stride_pick = order[:: max(1, int(np.ceil(lay.requested_tokens / budget_tokens)))]
     traces = np.sort(stride_pick)
-    qs, ks, vs, bt, sl = sample_inputs(traces)
-    t0 = time.perf_counter()
-    oracle.paged_decode_attn(qs, ks, vs, bt, sl)
-    t_attn = time.perf_counter() - t0
+    t_attn = 0.0
+    for layer in timed_layers:
+        qs, ks, vs, bt, sl = sample_inputs(traces, layer)
+        t0 = time.perf_counter()
+        oracle.paged_decode_attn(qs, ks, vs, bt, sl)
+        t_attn += time.perf_counter() - t0
     t0 = time.perf_counter()
     _, probs = oracle.step_score(sc.hidden, sc.boundary_idx, sc.W1, sc.b1, sc.W2, sc.b2, act=sc.act)
     ssum, cnt = sum0.copy(), cnt0.copy()
     scores = oracle.running_mean(sc.trace_of, probs.astype(np.float32), ssum, cnt)
     oracle.prune_free(scores, prune_k, lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy(), P)
     t_rest = time.perf_counter() - t0
-    total = t_attn * layers + t_rest   # several layers: one layer's attention timed, the rest extrapolated
+    scale = layers / len(timed_layers)
+    total = t_attn * scale + t_rest
+    how = "" if layers == 1 else " on layers %s, x%g: extrapolated to %d layers" % (timed_layers, scale, layers)
     return {
         "value": round(traces.size / total, 3), "unit": "trace-tokens/s", "cores": threads, "kind": "oracle",
-        "sample": "oracle attention on %d of %d traces (every %d-th by length, %d context tokens), plus the full "
-                  "scorer (B=%d), running mean and prune_free(k=%d); %.2f s attention per layer (x%d layers%s) + %.3f s rest" % (
-                      traces.size, s.N, max(1, len(order) // max(traces.size, 1)), int(sl.sum()),
-                      sc.boundary_idx.size, prune_k, t_attn, layers, ", extrapolated from layer 0" if layers > 1 else "",
-                      t_rest),
+        "sample": "oracle attention on %d of %d traces (every %d-th by length, %d context tokens)%s, plus the full "
+                  "scorer (B=%d), running mean and prune_free(k=%d); %.2f s attention measured + %.3f s rest" % (
+                      traces.size, s.N, max(1, len(order) // max(traces.size, 1)), int(sl.sum()), how,
+                      sc.boundary_idx.size, prune_k, t_attn, t_rest),
         "seconds": round(total, 3),
     }
 

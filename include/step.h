@@ -148,7 +148,12 @@ size_t step_score_workspace_bytes(const step_score_dims *dims);
  *   b1 [m] fp32 | W2 [m] bf16 | b2 [1] fp32 (device) | logits, probs [B] fp32
  *   trace_of [B] int32 | score_sum [N] fp32, score_cnt [N] int32 (in/out, or both NULL) | scores [N] fp32 or NULL
  * Arithmetic: bf16 products on the matrix cores with fp32 accumulation; the hidden activations
- * stay fp32.  logits within 1e-3 max-abs of the float64 definition.
+ * stay fp32.  logits within 1e-3 max-abs of the float64 definition.  m <= 16384.
+ * One kernel launch: the workgroups that split W1 hand their sums over through `workspace` and through
+ * arrival counters that belong to the library (device words that are zero between calls); every sum is
+ * taken in a fixed order, so results are bit-identical from call to call.  Each call takes the next of 64
+ * counter sets: calls on one stream, or up to 64 calls in flight on different streams of one GPU, do not
+ * interfere; a call recorded in a HIP graph keeps the set it was recorded with.
  */
 int step_score(const step_score_dims *dims, const uint16_t *hidden, const int32_t *boundary_idx,
                const uint16_t *W1, const float *b1, const uint16_t *W2, const float *b2,
@@ -257,17 +262,32 @@ int step_weighted_vote(int32_t N, const int32_t *answer, const float *scores, in
 int step_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------ */
-/* Measurement aid: per-kernel timing of attention's stage 1 (the HBM-streaming kernel).       */
-/* After step_attn_profile_begin(cap), each paged_decode_attn call attaches two HIP events from */
-/* a pool of `cap` pairs created by that call to its stage-1 kernel launch (they take the       */
-/* kernel's begin and end timestamps on the stream it launches on; calls beyond `cap` are not   */
-/* timed).  step_attn_profile_end waits for the                                                */
-/* recorded events, writes each bracketed call's stage-1 time in milliseconds to ms[0..n)      */
-/* (HOST array of capacity cap), destroys the pool and returns n, or -STEP_EINVAL.             */
-/* Benchmark use only: not thread safe, creates and destroys events.                           */
+/* Measurement aid: a bare read of KV tiles, to see what the memory system delivers to the       */
+/* access pattern of attention's streaming kernel with no arithmetic behind it.  k_pages and     */
+/* v_pages are pools [NP][Hkv][16][128] bf16 (4096-byte tiles).  `waves` x Hkv single-wave        */
+/* workgroups are launched; wave (w, g) reads the K and V tiles of KV head g of the pages          */
+/* page_ids[w * pages_per_wave .. + pages_per_wave) (device int32; ids outside [0, NP) read page */
+/* 0), two pages in flight.  pattern 0: 1 KB contiguous per load instruction; 1: the matrix-core */
+/* operand pattern.  nontemporal != 0: streaming (non-temporal) loads.  sink: one device word.   */
 /* ------------------------------------------------------------------------------------------ */
-int step_attn_profile_begin(int cap);
-int step_attn_profile_end(float *ms, int cap);
+int step_read_probe(const void *k_pages, const void *v_pages, const int32_t *page_ids, int32_t waves,
+                    int32_t pages_per_wave, int32_t Hkv, int32_t NP, int32_t pattern, int32_t nontemporal,
+                    uint32_t *sink, void *stream);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Measurement aid: the duration of every kernel the library launches.                          */
+/* After step_profile_begin(cap), each of the next `cap` kernel launches of any entry point      */
+/* carries two HIP events (from a pool of `cap` pairs created by that call) that take the         */
+/* kernel's begin and end timestamps on the stream it runs on; later launches are not timed.     */
+/* step_profile_end waits for the recorded events, writes for launch j < n, in launch order, the */
+/* kernel's id to kernel_ids[j] and its duration in milliseconds to ms[j] (HOST arrays of         */
+/* capacity cap), destroys the pool and returns n, or -STEP_EINVAL.                              */
+/* step_profile_kernel_name maps an id to a name (host pointer to a static string).              */
+/* Benchmark use only: not thread safe, creates and destroys events, not for graph capture.      */
+/* ------------------------------------------------------------------------------------------ */
+int step_profile_begin(int cap);
+int step_profile_end(int32_t *kernel_ids, float *ms, int cap);
+const char *step_profile_kernel_name(int id);
 
 #ifdef __cplusplus
 }

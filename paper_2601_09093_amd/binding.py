@@ -83,10 +83,14 @@ def lib():
     L.step_weighted_vote.argtypes = [i32] + [vp] * 6
     L.step_calib_copy.restype = ctypes.c_int
     L.step_calib_copy.argtypes = [vp, vp, sz, vp]
-    L.step_attn_profile_begin.restype = ctypes.c_int
-    L.step_attn_profile_begin.argtypes = [ctypes.c_int]
-    L.step_attn_profile_end.restype = ctypes.c_int
-    L.step_attn_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+    L.step_read_probe.restype = ctypes.c_int
+    L.step_read_probe.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
+    L.step_profile_begin.restype = ctypes.c_int
+    L.step_profile_begin.argtypes = [ctypes.c_int]
+    L.step_profile_end.restype = ctypes.c_int
+    L.step_profile_end.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+    L.step_profile_kernel_name.restype = ctypes.c_char_p
+    L.step_profile_kernel_name.argtypes = [ctypes.c_int]
     _lib = L
     return L
 
@@ -317,17 +321,30 @@ def calib_copy(dst, src):
     return dst
 
 
-def attn_profile_begin(cap):
-    """Bracket the stage-1 kernel of the next `cap` paged_decode_attn calls with HIP events."""
-    rc = lib().step_attn_profile_begin(int(cap))
+def read_probe(k_pages, v_pages, page_ids, waves, pages_per_wave, pattern, nontemporal, sink):
+    """Bare read of the K/V tiles of the listed pages by `waves` x Hkv waves (measurement aid)."""
+    NP, Hkv, P, D = k_pages.shape
+    if (P, D) != (16, 128) or page_ids.numel() < waves * pages_per_wave:
+        raise ValueError("read_probe wants [NP][Hkv][16][128] pools and waves * pages_per_wave page ids")
+    rc = lib().step_read_probe(_dev(k_pages, _BF16_OK, "k_pages"), _dev(v_pages, _BF16_OK, "v_pages"),
+                               _dev(page_ids, (torch.int32,), "page_ids"), int(waves), int(pages_per_wave), Hkv, NP,
+                               int(pattern), int(bool(nontemporal)), _dev(sink, (torch.int32,), "sink"), _stream())
     if rc != STEP_OK:
-        raise StepError(rc, "step_attn_profile_begin")
+        raise StepError(rc, "step_read_probe")
 
 
-def attn_profile_end(cap):
-    """Milliseconds of each bracketed stage-1 kernel since attn_profile_begin (host list)."""
-    buf = (ctypes.c_float * int(cap))()
-    n = lib().step_attn_profile_end(buf, int(cap))
+def profile_begin(cap):
+    """Attach HIP events to each of the next `cap` kernel launches of the library (benchmarks only)."""
+    rc = lib().step_profile_begin(int(cap))
+    if rc != STEP_OK:
+        raise StepError(rc, "step_profile_begin")
+
+
+def profile_end(cap):
+    """[(kernel name, milliseconds)] of the launches timed since profile_begin, in launch order."""
+    ids = (ctypes.c_int32 * int(cap))()
+    ms = (ctypes.c_float * int(cap))()
+    n = lib().step_profile_end(ids, ms, int(cap))
     if n < 0:
-        raise StepError(-n, "step_attn_profile_end")
-    return [float(buf[i]) for i in range(n)]
+        raise StepError(-n, "step_profile_end")
+    return [(lib().step_profile_kernel_name(int(ids[i])).decode(), float(ms[i])) for i in range(n)]

@@ -113,12 +113,6 @@ Layout layout_for(const step_attn_dims *d)
     return l;
 }
 
-// optional per-call event pairs around stage 1 (benchmarks only)
-struct Profile {
-    hipEvent_t *ev = nullptr;  // 2 * cap events
-    int cap = 0, used = 0;
-} g_prof;
-
 enum : int { kDoPlan = 1, kDoAttend = 2 };
 
 int launch(const AttnArgs &a, int D, hipStream_t s, int what)
@@ -127,12 +121,6 @@ int launch(const AttnArgs &a, int D, hipStream_t s, int what)
     if (what & kDoAttend) {
         // one call: every wave of attn_front finds its block's shared prefix itself; planned: they are in the workspace
         launch_front(a, D, (what & kDoPlan) != 0, s);
-        // when profiling, the stage-1 launch carries its own start/stop events: they take the
-        // kernel's begin and end timestamps, with no marker processing inside the interval
-        const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
-        hipEvent_t e0 = timed ? g_prof.ev[2 * g_prof.used] : nullptr;
-        hipEvent_t e1 = timed ? g_prof.ev[2 * g_prof.used + 1] : nullptr;
-        if (timed) ++g_prof.used;
         // G == 4, D == 128: the dot2 kernel (about 1 % ahead of the matrix-core kernel at that shape; at
         // D == 64 the matrix-core kernel is the faster one, 6.2 against 5.5 TB/s);
         // STEP_ATTN_G4_MFMA=1, read once, sends that shape to the matrix-core kernel too (testing aid)
@@ -140,8 +128,8 @@ int launch(const AttnArgs &a, int D, hipStream_t s, int what)
             const char *e = getenv("STEP_ATTN_G4_MFMA");
             return e && e[0] == '1';
         }();
-        if (a.Hq / a.Hkv == 4 && D == 128 && !g4_mfma) launch_stream_g4(a, s, e0, e1);
-        else launch_stream_mfma(a, D, s, e0, e1);
+        if (a.Hq / a.Hkv == 4 && D == 128 && !g4_mfma) launch_stream_g4(a, s);
+        else launch_stream_mfma(a, D, s);
         launch_merge(a, D, s);
     }
     return launch_status();
@@ -224,29 +212,4 @@ extern "C" int paged_decode_attn_planned(const step_attn_dims *d, const uint16_t
 {
     return run(d, q, k_pages, v_pages, block_tables, seq_lens, out, workspace, workspace_bytes, status, stream,
                kDoAttend);
-}
-
-extern "C" int step_attn_profile_begin(int cap)
-{
-    if (cap <= 0 || g_prof.ev) return STEP_EINVAL;
-    g_prof.ev = new hipEvent_t[2 * (size_t)cap];
-    for (int i = 0; i < 2 * cap; ++i)
-        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return STEP_ELAUNCH;
-    g_prof.cap = cap;
-    g_prof.used = 0;
-    return STEP_OK;
-}
-
-extern "C" int step_attn_profile_end(float *ms, int cap)
-{
-    if (!g_prof.ev || !ms || cap < g_prof.used) return -STEP_EINVAL;
-    const int n = g_prof.used;
-    for (int i = 0; i < n; ++i) {
-        (void)hipEventSynchronize(g_prof.ev[2 * i + 1]);
-        if (hipEventElapsedTime(&ms[i], g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess) ms[i] = -1.f;
-    }
-    for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
-    delete[] g_prof.ev;
-    g_prof = Profile();
-    return n;
 }

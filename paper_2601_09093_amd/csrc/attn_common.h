@@ -17,8 +17,6 @@
 //   Every wave derives its own run from seq_lens and S_b with two prefix sums (plan_build): there is no
 //   planning kernel and no record array.
 #pragma once
-#include <hip/hip_ext.h>
-
 #include "common.h"
 
 namespace step {
@@ -321,12 +319,11 @@ struct RunWalker {
     }
 };
 
-// Host-side launchers, one per translation unit.  D is the head dimension (64 or 128); e0 / e1, when
-// not null, are recorded at the start and the end of the stage-1 kernel (benchmarks only).
+// Host-side launchers, one per translation unit.  D is the head dimension (64 or 128).
 void launch_front(const AttnArgs &a, int D, bool detect, hipStream_t s);                    // attn_front.hip
 void launch_plan_blocks(const AttnArgs &a, hipStream_t s);                                  // attn_front.hip
-void launch_stream_mfma(const AttnArgs &a, int D, hipStream_t s, hipEvent_t e0, hipEvent_t e1);  // attn_mfma.hip
-void launch_stream_g4(const AttnArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1);      // attn_g4.hip (D = 128, G = 4)
+void launch_stream_mfma(const AttnArgs &a, int D, hipStream_t s);                           // attn_mfma.hip
+void launch_stream_g4(const AttnArgs &a, hipStream_t s);                                    // attn_g4.hip (D = 128, G = 4)
 int stream_g4_waves_per_cu();                                                               // attn_g4.hip
 void launch_merge(const AttnArgs &a, int D, hipStream_t s);                                 // attn_merge.hip
 

@@ -306,11 +306,9 @@ __global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
 
 }  // namespace
 
-void launch_stream_g4(const AttnArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
+void launch_stream_g4(const AttnArgs &a, hipStream_t s)
 {
-    const dim3 grid((u32)(a.Wh * a.Hkv));
-    if (e0) hipExtLaunchKernelGGL((attn_partial_g4<128>), grid, dim3(64), 0, s, e0, e1, 0, a);
-    else hipLaunchKernelGGL((attn_partial_g4<128>), grid, dim3(64), 0, s, a);
+    launch_kernel(kKernStage1, attn_partial_g4<128>, dim3((u32)(a.Wh * a.Hkv)), dim3(64), s, a);
 }
 
 // resident waves of the streaming kernel per compute unit, from the occupancy query (8 if it fails)

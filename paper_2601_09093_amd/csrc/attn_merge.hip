@@ -95,14 +95,14 @@ void launch_merge(const AttnArgs &a, int D, hipStream_t s)
     const dim3 grid((u32)(a.N * a.Hq));
     const int key = D * 16 + a.Hq / a.Hkv;
     switch (key) {
-        case 64 * 16 + 1: hipLaunchKernelGGL((attn_merge<64, 1>), grid, dim3(64), 0, s, a); break;
-        case 64 * 16 + 2: hipLaunchKernelGGL((attn_merge<64, 2>), grid, dim3(64), 0, s, a); break;
-        case 64 * 16 + 4: hipLaunchKernelGGL((attn_merge<64, 4>), grid, dim3(64), 0, s, a); break;
-        case 64 * 16 + 8: hipLaunchKernelGGL((attn_merge<64, 8>), grid, dim3(64), 0, s, a); break;
-        case 128 * 16 + 1: hipLaunchKernelGGL((attn_merge<128, 1>), grid, dim3(64), 0, s, a); break;
-        case 128 * 16 + 2: hipLaunchKernelGGL((attn_merge<128, 2>), grid, dim3(64), 0, s, a); break;
-        case 128 * 16 + 4: hipLaunchKernelGGL((attn_merge<128, 4>), grid, dim3(64), 0, s, a); break;
-        case 128 * 16 + 8: hipLaunchKernelGGL((attn_merge<128, 8>), grid, dim3(64), 0, s, a); break;
+        case 64 * 16 + 1: launch_kernel(kKernMerge, attn_merge<64, 1>, grid, dim3(64), s, a); break;
+        case 64 * 16 + 2: launch_kernel(kKernMerge, attn_merge<64, 2>, grid, dim3(64), s, a); break;
+        case 64 * 16 + 4: launch_kernel(kKernMerge, attn_merge<64, 4>, grid, dim3(64), s, a); break;
+        case 64 * 16 + 8: launch_kernel(kKernMerge, attn_merge<64, 8>, grid, dim3(64), s, a); break;
+        case 128 * 16 + 1: launch_kernel(kKernMerge, attn_merge<128, 1>, grid, dim3(64), s, a); break;
+        case 128 * 16 + 2: launch_kernel(kKernMerge, attn_merge<128, 2>, grid, dim3(64), s, a); break;
+        case 128 * 16 + 4: launch_kernel(kKernMerge, attn_merge<128, 4>, grid, dim3(64), s, a); break;
+        case 128 * 16 + 8: launch_kernel(kKernMerge, attn_merge<128, 8>, grid, dim3(64), s, a); break;
     }
 }
 

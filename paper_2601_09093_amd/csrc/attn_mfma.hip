@@ -461,36 +461,27 @@ void launch_front(const AttnArgs &a, int D, bool detect, hipStream_t s)
 {
     if (!a.prefix_qt) return;
     const dim3 grid((u32)(a.Hkv * a.nblk * a.pmax));  // units beyond a block's sub-chunks exit once they know S_b
-#define STEP_FRONT(DD, QQ)                                                                     \
-    do {                                                                                       \
-        if (detect) hipLaunchKernelGGL((attn_front<DD, QQ, true>), grid, dim3(64), 0, s, a);   \
-        else hipLaunchKernelGGL((attn_front<DD, QQ, false>), grid, dim3(64), 0, s, a);         \
-    } while (0)
+    void (*kernel)(AttnArgs);
     if (D == 128) {
-        if (a.prefix_qt == 2) STEP_FRONT(128, 2);
-        else STEP_FRONT(128, 1);
+        if (a.prefix_qt == 2) kernel = detect ? attn_front<128, 2, true> : attn_front<128, 2, false>;
+        else kernel = detect ? attn_front<128, 1, true> : attn_front<128, 1, false>;
     } else {
-        if (a.prefix_qt == 2) STEP_FRONT(64, 2);
-        else STEP_FRONT(64, 1);
+        if (a.prefix_qt == 2) kernel = detect ? attn_front<64, 2, true> : attn_front<64, 2, false>;
+        else kernel = detect ? attn_front<64, 1, true> : attn_front<64, 1, false>;
     }
-#undef STEP_FRONT
+    launch_kernel(kKernFront, kernel, grid, dim3(64), s, a);
 }
 
 void launch_plan_blocks(const AttnArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(attn_plan_blocks, dim3((u32)a.nblk), dim3(64), 0, s, a);
+    launch_kernel(kKernPlanBlocks, attn_plan_blocks, dim3((u32)a.nblk), dim3(64), s, a);
 }
 
-void launch_stream_mfma(const AttnArgs &a, int D, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
+void launch_stream_mfma(const AttnArgs &a, int D, hipStream_t s)
 {
     const dim3 grid((u32)(a.Wh * a.Hkv));
-    if (D == 128) {
-        if (e0) hipExtLaunchKernelGGL((attn_partial_mfma<128>), grid, dim3(64), 0, s, e0, e1, 0, a);
-        else hipLaunchKernelGGL((attn_partial_mfma<128>), grid, dim3(64), 0, s, a);
-    } else {
-        if (e0) hipExtLaunchKernelGGL((attn_partial_mfma<64>), grid, dim3(64), 0, s, e0, e1, 0, a);
-        else hipLaunchKernelGGL((attn_partial_mfma<64>), grid, dim3(64), 0, s, a);
-    }
+    if (D == 128) launch_kernel(kKernStage1, attn_partial_mfma<128>, grid, dim3(64), s, a);
+    else launch_kernel(kKernStage1, attn_partial_mfma<64>, grid, dim3(64), s, a);
 }
 
 }  // namespace attn

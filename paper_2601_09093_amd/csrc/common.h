@@ -1,6 +1,7 @@
 // Shared device/host helpers of libstep (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "step.h"
@@ -88,6 +89,37 @@ __device__ __forceinline__ int block_excl_scan(int v, int *scratch /*[32]*/, int
     const int base = wid > 0 ? scratch[16 + wid - 1] : 0;
     *total = scratch[31];
     return base + x - v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Every kernel of the library is launched through launch_kernel.  While a profiling session is open
+// (step_profile_begin, benchmarks only) the launch carries two HIP events that take the kernel's own begin
+// and end timestamps on the stream it runs on; otherwise it is a plain launch.
+// ---------------------------------------------------------------------------------------------
+enum KernelId {
+    kKernFront = 0, kKernPlanBlocks, kKernStage1, kKernMerge, kKernScore, kKernScoreFinish, kKernPruneFused,
+    kKernPruneSelect, kKernPruneRelease, kKernPruneCompact, kKernReserve, kKernAppend, kKernVote, kKernCopy,
+    kKernReadProbe, kKernCount
+};
+
+struct Profile {
+    hipEvent_t *ev = nullptr;  // 2 * cap events
+    int32_t *ids = nullptr;    // kernel id of each timed launch
+    int cap = 0, used = 0;
+};
+Profile &profile();  // misc.hip
+
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(int id, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s, Args &&...args)
+{
+    Profile &p = profile();
+    if (p.ev && p.used < p.cap) {
+        const int i = p.used++;
+        p.ids[i] = id;
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, p.ev[2 * i], p.ev[2 * i + 1], 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+    }
 }
 
 inline int launch_status()

@@ -349,7 +349,7 @@ extern "C" int step_reserve_pages(int32_t N, int32_t MAXB, int32_t NP, int32_t P
     a.bitmap = reinterpret_cast<u32 *>(workspace);
     a.N = N; a.MAXB = MAXB; a.NP = NP; a.P = P;
     a.words = (int)((((size_t)NP + 63) / 64) * 2);
-    hipLaunchKernelGGL(reserve_pages_kernel, dim3(1), dim3(kThreads), 0, reinterpret_cast<hipStream_t>(stream), a);
+    launch_kernel(kKernReserve, reserve_pages_kernel, dim3(1), dim3(kThreads), reinterpret_cast<hipStream_t>(stream), a);
     return launch_status();
 }
 
@@ -366,7 +366,7 @@ extern "C" int step_append_kv(const step_attn_dims *d, const uint16_t *k_new, co
     a.k_new = k_new; a.v_new = v_new; a.k_pages = k_pages; a.v_pages = v_pages;
     a.block_tables = block_tables; a.refcounts = refcounts; a.seq_lens = seq_lens; a.status = status;
     a.N = d->N; a.Hkv = d->Hkv; a.D = d->D; a.MAXB = d->MAXB; a.NP = d->NP;
-    hipLaunchKernelGGL(append_kv_kernel, dim3(d->N), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), a);
+    launch_kernel(kKernAppend, append_kv_kernel, dim3(d->N), dim3(256), reinterpret_cast<hipStream_t>(stream), a);
     return launch_status();
 }
 
@@ -375,7 +375,7 @@ extern "C" int step_weighted_vote(int32_t N, const int32_t *answer, const float 
 {
     if (N < 0 || N > kMaxN || !winner || !weight) return STEP_EINVAL;
     if (N > 0 && (!answer || !scores)) return STEP_EINVAL;
-    hipLaunchKernelGGL(weighted_vote_kernel, dim3(1), dim3(kThreads), 0, reinterpret_cast<hipStream_t>(stream), N,
-                       answer, scores, winner, weight, status);
+    launch_kernel(kKernVote, weighted_vote_kernel, dim3(1), dim3(kThreads), reinterpret_cast<hipStream_t>(stream), N,
+                  answer, scores, winner, weight, status);
     return launch_status();
 }

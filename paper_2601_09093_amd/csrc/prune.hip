@@ -330,13 +330,13 @@ int run_prune(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *score
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     static const bool force_multi = getenv("STEP_PRUNE_MULTI") != nullptr;  // testing aid: always three kernels
     if (!force_multi && N <= kFusedN && a.words <= kFusedWords && (long long)k * MAXB <= kFusedEntries) {
-        hipLaunchKernelGGL(prune_fused, dim3(1), dim3(kSelThreads), 0, s, a);
+        launch_kernel(kKernPruneFused, prune_fused, dim3(1), dim3(kSelThreads), s, a);
         return launch_status();
     }
-    hipLaunchKernelGGL(prune_select, dim3(1), dim3(kSelThreads), 0, s, a);
+    launch_kernel(kKernPruneSelect, prune_select, dim3(1), dim3(kSelThreads), s, a);
     if (k > 0 && MAXB > 0)
-        hipLaunchKernelGGL(prune_release, dim3((MAXB + 255) / 256, k), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(prune_compact, dim3(1), dim3(kSelThreads), 0, s, a);
+        launch_kernel(kKernPruneRelease, prune_release, dim3((MAXB + 255) / 256, k), dim3(256), s, a);
+    launch_kernel(kKernPruneCompact, prune_compact, dim3(1), dim3(kSelThreads), s, a);
     return launch_status();
 }
 

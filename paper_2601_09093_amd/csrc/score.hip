@@ -3,30 +3,49 @@
 // step boundary, followed by the running-average trace score of Section 4.3 ("Update score_t" in
 // Algorithm 1).
 //
-// score_hidden: the dense projection W1 X^T on the matrix cores (v_mfma_f32_16x16x32_bf16).  One
-//   workgroup owns 16 rows of W1 (one MFMA tile of hidden units) and up to 32 boundaries; its
-//   sixteen waves split the contraction over d, 128 values per iteration, and are summed through LDS.  The
-//   gather hidden[boundary_idx[b]] is fused into the B-operand loads.  Bias, activation and the
-//   product with the 16 matching entries of W2 follow in registers; the workgroup writes one
-//   partial logit per boundary.
-// score_finish: adds the partial logits in a fixed order, applies the sigmoid, then one thread
-//   replays the boundaries in index order to update (sum, count) per trace -- fp32 addition is
-//   not associative and a trace may own several boundaries, so the order is part of the result.
+// One kernel, score_hidden, grid (m / 16 row tiles, chunks of the contraction over d, tiles of 32 boundaries):
+//   1. a workgroup of four waves owns 16 rows of W1 (one MFMA tile of hidden units), one chunk of d and up to
+//      32 boundaries; its waves split the chunk, 128 values per iteration (v_mfma_f32_16x16x32_bf16), the gather
+//      hidden[boundary_idx[b]] fused into the B-operand loads, and are summed through LDS.  With one chunk
+//      the workgroup goes straight to step 3 with its sums in LDS; otherwise it stores them.
+//   2. the last workgroup of a row tile to arrive (a ticket per tile) adds the chunks in chunk order,
+//   3. applies bias and activation, multiplies by the 16 matching entries of W2 and stores one partial logit
+//      per boundary.
+//   4. the last workgroup of the launch to arrive adds the partial logits in tile order, applies the sigmoid,
+//      then one thread replays the boundaries in index order to update (sum, count) per trace -- fp32 addition
+//      is not associative and a trace may own several boundaries, so the order is part of the result -- and
+//      the scores are refreshed.
+// The split over d puts at least 256 workgroups on the W1 stream whatever m is (the paper's m = 512 gives only
+// 32 row tiles); every sum is taken in a fixed order, so the result does not depend on which workgroup arrives last.
+// The tickets are library-owned device words that start at zero and are put back to zero by the workgroup that
+// finds itself last; each call takes the next of kTicketSets sets, so calls that overlap on different streams
+// do not meet unless more than kTicketSets of them are in flight.
+#include <atomic>
+
 #include "common.h"
 
 namespace step {
 namespace {
 
-constexpr int kWaves = 16;  // the contraction over d is split over the waves of a workgroup
-constexpr int kBT = 2;  // boundary tiles (of 16) per workgroup
+constexpr int kWaves = 4;          // the chunk of d is split over the waves of a workgroup
+constexpr int kBT = 2;             // boundary tiles (of 16) per workgroup
+constexpr int kMaxRowTiles = 1024; // m <= 16384
+constexpr int kTicketSets = 64;
+constexpr int kTicketsPerSet = 2 * kMaxRowTiles + 1;  // a row-tile ticket per (tile of 32 boundaries <= 2, row tile), one for the launch
+
+__device__ int32_t score_tickets[kTicketSets][kTicketsPerSet];
 
 struct ScoreArgs {
     const uint16_t *hidden, *W1, *W2;
     const int32_t *boundary_idx, *trace_of;
     const float *b1, *b2;
-    float *logits, *probs, *score_sum, *scores, *partial;  // partial [m/16][B]
+    float *logits, *probs, *score_sum, *scores;
+    float *partial;  // [chunks][row tiles][B][16] sums of one chunk of d (only with more than one chunk)
+    float *plogit;   // [row tiles][B] partial logits
     int32_t *score_cnt, *status;
     int R, d, m, B, N, act;
+    int nchunk, chunk_iters;  // chunks of d, iterations (128 values) per chunk
+    int set;                  // ticket set of this call
 };
 
 __device__ __forceinline__ float activate(float z, int act)
@@ -35,13 +54,128 @@ __device__ __forceinline__ float activate(float z, int act)
     return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
 }
 
-__global__ __launch_bounds__(64 * kWaves) void score_hidden(const ScoreArgs a)
+constexpr int kFinishChunk = 1024;  // boundaries whose (trace, prob) are staged in LDS at a time
+constexpr int kStateMax = 2048;     // traces whose (sum, count) state is staged in LDS
+constexpr int kThreads = 64 * kWaves;
+
+// Words that workgroups of one launch hand to each other are stored and loaded at device scope (the
+// compute dies have caches of their own, which these accesses go past), so no cache has to be written back
+// or invalidated as a whole, which is what a device-wide fence would do.
+__device__ __forceinline__ void st_dev(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float *p)
+{
+    return __hip_atomic_load(const_cast<float *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// true in every thread of the workgroup that is the last of `expected` to take the ticket; that workgroup
+// puts the ticket back to zero.  Every thread first waits until its own device-scope stores have been
+// acknowledged, then the workgroup meets, then one thread takes the ticket: whoever is last therefore finds
+// the words of all earlier arrivals when it loads them at device scope.
+__device__ __forceinline__ bool last_to_arrive(int32_t *ticket, int expected, int *flag_s)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = old == expected - 1;
+        if (last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag_s = last ? 1 : 0;
+    }
+    __syncthreads();
+    return *flag_s != 0;
+}
+
+// step 4 (also the whole kernel when B == 0): logits, probabilities, running mean, scores
+__device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, float *sum_s, int *cnt_s)
+{
+    const int tid = threadIdx.x;
+    const int mt = a.m / 16;
+    const float b2 = a.b2[0];
+    const bool state = a.score_sum != nullptr;
+    const bool staged = state && a.N <= kStateMax;  // keep the sequential replay off global memory
+    if (staged)
+        for (int t = tid; t < a.N; t += kThreads) {
+            sum_s[t] = a.score_sum[t];
+            cnt_s[t] = a.score_cnt[t];
+        }
+    for (int base = 0; base < a.B; base += kFinishChunk) {
+        const int nbd = min(kFinishChunk, a.B - base);
+        for (int bb = tid; bb < nbd; bb += kThreads) {
+            const int b = base + bb;
+            // partial logits are summed in a fixed order, four independent accumulators in flight
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int t = 0;
+            for (; t + 3 < mt; t += 4) {
+                s0 += ld_dev(&a.plogit[(size_t)(t + 0) * a.B + b]);
+                s1 += ld_dev(&a.plogit[(size_t)(t + 1) * a.B + b]);
+                s2 += ld_dev(&a.plogit[(size_t)(t + 2) * a.B + b]);
+                s3 += ld_dev(&a.plogit[(size_t)(t + 3) * a.B + b]);
+            }
+            for (; t < mt; ++t) s0 += ld_dev(&a.plogit[(size_t)t * a.B + b]);
+            const float logit = b2 + ((s0 + s1) + (s2 + s3));
+            const float prob = 1.0f / (1.0f + expf(-logit));
+            a.logits[b] = logit;
+            a.probs[b] = prob;
+            prob_s[bb] = prob;
+            trace_s[bb] = state ? a.trace_of[b] : 0;
+        }
+        if (!state) continue;  // uniform
+        __syncthreads();
+        if (tid == 0) {
+            // boundaries in index order: fp32 addition is not associative and a trace may own several
+            for (int bb = 0; bb < nbd; ++bb) {
+                const int t = trace_s[bb];
+                if ((u32)t >= (u32)a.N) {
+                    report(a.status, STEP_EINDEX);
+                    continue;
+                }
+                if (staged) {
+                    sum_s[t] = sum_s[t] + prob_s[bb];
+                    cnt_s[t] = cnt_s[t] + 1;
+                } else {
+                    a.score_sum[t] = a.score_sum[t] + prob_s[bb];
+                    a.score_cnt[t] = a.score_cnt[t] + 1;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (!state) return;
+    __threadfence_block();
+    __syncthreads();
+    for (int t = tid; t < a.N; t += kThreads) {
+        float sm;
+        int n;
+        if (staged) {
+            sm = sum_s[t];
+            n = cnt_s[t];
+            a.score_sum[t] = sm;
+            a.score_cnt[t] = n;
+        } else {
+            sm = a.score_sum[t];
+            n = a.score_cnt[t];
+        }
+        if (a.scores) a.scores[t] = n > 0 ? sm / (float)n : INFINITY;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
 {
     __shared__ float red[kWaves][kBT][4][64];
+    __shared__ float prob_s[kFinishChunk];
+    __shared__ int trace_s[kFinishChunk];
+    __shared__ float sum_s[kStateMax];
+    __shared__ int cnt_s[kStateMax];
+    __shared__ int flag_s;
+    if (a.B == 0) {  // nothing to score: the scores are refreshed from the state
+        score_finish(a, prob_s, trace_s, sum_s, cnt_s);
+        return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int row16 = lane & 15, kg = lane >> 4;
-    const int m0 = blockIdx.x * 16;
-    const int b0 = blockIdx.y * (16 * kBT);
+    const int mt = blockIdx.x, MT = gridDim.x, chunk = blockIdx.y, bz = blockIdx.z;
+    const int m0 = mt * 16;
+    const int b0 = bz * (16 * kBT);
 
     // rows of `hidden` feeding the B operand of each boundary tile (column = lane % 16)
     const uint16_t *xrow[kBT];
@@ -52,7 +186,7 @@ __global__ __launch_bounds__(64 * kWaves) void score_hidden(const ScoreArgs a)
         if (b < a.B) {
             rix = a.boundary_idx[b];
             if ((u32)rix >= (u32)a.R) {
-                if (blockIdx.x == 0 && kg == 0 && w == 0) report(a.status, STEP_EINDEX);
+                if (mt == 0 && chunk == 0 && kg == 0 && w == 0) report(a.status, STEP_EINDEX);
                 rix = 0;
             }
         }
@@ -62,8 +196,8 @@ __global__ __launch_bounds__(64 * kWaves) void score_hidden(const ScoreArgs a)
     const uint16_t *wrow = a.W1 + (size_t)(m0 + row16) * a.d;
 
     f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
-    const int iters = a.d / 128;
-    for (int it = w; it < iters; it += kWaves) {
+    const int it0 = chunk * a.chunk_iters, it1 = min(it0 + a.chunk_iters, a.d / 128);
+    for (int it = it0 + w; it < it1; it += kWaves) {
         // the contraction index is permuted identically for both operands: lane group kg takes the
         // 32 consecutive values kbase + 32 kg .. +32, eight per MFMA, so a lane reads 64 contiguous
         // bytes per iteration and the four groups cover 256 contiguous bytes of the row
@@ -98,109 +232,72 @@ __global__ __launch_bounds__(64 * kWaves) void score_hidden(const ScoreArgs a)
         red[w][1][i][lane] = c1[i];
     }
     __syncthreads();
+    // this workgroup's sums of its chunk: wave t < kBT takes boundary tile t; z[i] belongs to hidden unit
+    // m0 + 4 kg + i and boundary b
+    const int b = b0 + w * 16 + row16;
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
     if (w < kBT) {
-        const int b = b0 + w * 16 + row16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) z[i] += red[ww][w][i][lane];
+    }
+    int32_t *tickets = score_tickets[a.set];
+    if (a.nchunk > 1) {
+        // step 1 -> 2: store the chunk's sums; the tile's last chunk to arrive adds all of them in chunk order
+        if (w < kBT && b < a.B) {
+            float *dst = a.partial + (((size_t)chunk * MT + mt) * a.B + b) * 16 + kg * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st_dev(dst + i, z[i]);
+        }
+        if (!last_to_arrive(&tickets[bz * MT + mt], a.nchunk, &flag_s)) return;
+        if (w < kBT && b < a.B) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) z[i] = 0.f;
+            for (int ch = 0; ch < a.nchunk; ++ch) {
+                const float *src = a.partial + (((size_t)ch * MT + mt) * a.B + b) * 16 + kg * 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) z[i] += ld_dev(src + i);
+            }
+        }
+    }
+    // step 3
+    if (w < kBT) {
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = m0 + kg * 4 + i;
-            float z = a.b1[row];
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) z += red[ww][w][i][lane];
-            s = fmaf(bf16_lo((u32)a.W2[row]), activate(z, a.act), s);
+            s = fmaf(bf16_lo((u32)a.W2[row]), activate(z[i] + a.b1[row], a.act), s);
         }
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
-        if (kg == 0 && b < a.B) a.partial[(size_t)blockIdx.x * a.B + b] = s;
+        if (kg == 0 && b < a.B) st_dev(&a.plogit[(size_t)mt * a.B + b], s);
     }
+    // step 4
+    if (!last_to_arrive(&tickets[kTicketsPerSet - 1], (int)(MT * gridDim.z), &flag_s)) return;
+    score_finish(a, prob_s, trace_s, sum_s, cnt_s);
 }
 
-constexpr int kFinishThreads = 256;
-constexpr int kFinishChunk = 1024;  // boundaries whose (trace, prob) are staged in LDS at a time
-constexpr int kStateMax = 2048;     // traces whose (sum, count) state is staged in LDS
+std::atomic<unsigned> g_next_set{0};
 
-__global__ __launch_bounds__(kFinishThreads) void score_finish(const ScoreArgs a)
+// chunks of the contraction over d: enough workgroups to stream W1 from the whole chip when there are few
+// row tiles and few boundaries
+void chunking(const step_score_dims *d, int &nchunk, int &chunk_iters)
 {
-    __shared__ float prob_s[kFinishChunk];
-    __shared__ int trace_s[kFinishChunk];
-    __shared__ float sum_s[kStateMax];
-    __shared__ int cnt_s[kStateMax];
-    const int tid = threadIdx.x;
-    const int mt = a.m / 16;
-    const float b2 = a.b2[0];
-    const bool state = a.score_sum != nullptr;
-    const bool staged = state && a.N <= kStateMax;  // keep the sequential replay off global memory
-    if (staged)
-        for (int t = tid; t < a.N; t += kFinishThreads) {
-            sum_s[t] = a.score_sum[t];
-            cnt_s[t] = a.score_cnt[t];
-        }
-    for (int base = 0; base < a.B; base += kFinishChunk) {
-        const int nbd = min(kFinishChunk, a.B - base);
-        for (int bb = tid; bb < nbd; bb += kFinishThreads) {
-            const int b = base + bb;
-            // partial logits are summed in a fixed order, four independent accumulators in flight
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-            int t = 0;
-            for (; t + 3 < mt; t += 4) {
-                s0 += a.partial[(size_t)(t + 0) * a.B + b];
-                s1 += a.partial[(size_t)(t + 1) * a.B + b];
-                s2 += a.partial[(size_t)(t + 2) * a.B + b];
-                s3 += a.partial[(size_t)(t + 3) * a.B + b];
-            }
-            for (; t < mt; ++t) s0 += a.partial[(size_t)t * a.B + b];
-            const float logit = b2 + ((s0 + s1) + (s2 + s3));
-            const float prob = 1.0f / (1.0f + expf(-logit));
-            a.logits[b] = logit;
-            a.probs[b] = prob;
-            prob_s[bb] = prob;
-            trace_s[bb] = state ? a.trace_of[b] : 0;
-        }
-        if (!state) continue;  // uniform
-        __syncthreads();
-        if (tid == 0) {
-            // boundaries in index order: fp32 addition is not associative and a trace may own several
-            for (int bb = 0; bb < nbd; ++bb) {
-                const int t = trace_s[bb];
-                if ((u32)t >= (u32)a.N) {
-                    report(a.status, STEP_EINDEX);
-                    continue;
-                }
-                if (staged) {
-                    sum_s[t] = sum_s[t] + prob_s[bb];
-                    cnt_s[t] = cnt_s[t] + 1;
-                } else {
-                    a.score_sum[t] = a.score_sum[t] + prob_s[bb];
-                    a.score_cnt[t] = a.score_cnt[t] + 1;
-                }
-            }
-        }
-        __syncthreads();
-    }
-    if (!state) return;
-    __threadfence_block();
-    __syncthreads();
-    for (int t = tid; t < a.N; t += kFinishThreads) {
-        float sm;
-        int n;
-        if (staged) {
-            sm = sum_s[t];
-            n = cnt_s[t];
-            a.score_sum[t] = sm;
-            a.score_cnt[t] = n;
-        } else {
-            sm = a.score_sum[t];
-            n = a.score_cnt[t];
-        }
-        if (a.scores) a.scores[t] = n > 0 ? sm / (float)n : INFINITY;
-    }
+    const int iters = d->d / 128, MT = d->m / 16;
+    const int nbz = d->B > 0 ? (d->B + 16 * kBT - 1) / (16 * kBT) : 1;
+    int want = 1;
+    if (nbz <= 2 && MT * nbz < 256) want = (256 + MT * nbz - 1) / (MT * nbz);
+    if (want > iters) want = iters;
+    chunk_iters = (iters + want - 1) / want;
+    nchunk = (iters + chunk_iters - 1) / chunk_iters;
 }
 
 bool dims_ok(const step_score_dims *d)
 {
     if (!d) return false;
     if (d->R < 0 || d->d <= 0 || d->m <= 0 || d->B < 0 || d->N < 0) return false;
-    if (d->d % 128 || d->m % 16) return false;
+    if (d->d % 128 || d->m % 16 || d->m / 16 > kMaxRowTiles) return false;
     if (d->act != STEP_ACT_RELU && d->act != STEP_ACT_GELU) return false;
     if (d->B > 0 && d->R == 0) return false;
     if (d->B > (1 << 20)) return false;
@@ -215,7 +312,12 @@ using namespace step;
 extern "C" size_t step_score_workspace_bytes(const step_score_dims *d)
 {
     if (!dims_ok(d)) return 0;
-    return (((size_t)(d->m / 16) * (size_t)(d->B > 0 ? d->B : 1) * sizeof(float)) + 255) & ~(size_t)255;
+    int nchunk, chunk_iters;
+    chunking(d, nchunk, chunk_iters);
+    const size_t B = d->B > 0 ? d->B : 1, MT = d->m / 16;
+    const size_t plogit = (MT * B * sizeof(float) + 255) & ~(size_t)255;
+    const size_t partial = nchunk > 1 ? (((size_t)nchunk * MT * B * 16 * sizeof(float)) + 255) & ~(size_t)255 : 0;
+    return plogit + partial;
 }
 
 extern "C" int step_score(const step_score_dims *d, const uint16_t *hidden, const int32_t *boundary_idx,
@@ -237,15 +339,20 @@ extern "C" int step_score(const step_score_dims *d, const uint16_t *hidden, cons
     ScoreArgs a;
     a.hidden = hidden; a.W1 = W1; a.W2 = W2; a.boundary_idx = boundary_idx; a.trace_of = trace_of;
     a.b1 = b1; a.b2 = b2; a.logits = logits; a.probs = probs; a.score_sum = score_sum; a.scores = scores;
-    a.partial = reinterpret_cast<float *>(workspace);
     a.score_cnt = score_cnt; a.status = status;
     a.R = d->R; a.d = d->d; a.m = d->m; a.B = d->B; a.N = d->N; a.act = d->act;
+    chunking(d, a.nchunk, a.chunk_iters);
+    const size_t MT = d->m / 16, Bp = d->B > 0 ? d->B : 1;
+    a.plogit = reinterpret_cast<float *>(workspace);
+    a.partial = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ((MT * Bp * sizeof(float) + 255) & ~(size_t)255));
+    a.set = (int)(g_next_set.fetch_add(1, std::memory_order_relaxed) % kTicketSets);
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (d->B > 0) {
-        const dim3 grid(d->m / 16, (d->B + 16 * kBT - 1) / (16 * kBT));
-        hipLaunchKernelGGL(score_hidden, grid, dim3(64 * kWaves), 0, s, a);
+        const dim3 grid(d->m / 16, a.nchunk, (d->B + 16 * kBT - 1) / (16 * kBT));
+        launch_kernel(kKernScore, score_hidden, grid, dim3(kThreads), s, a);
+    } else if (state && scores) {
+        launch_kernel(kKernScore, score_hidden, dim3(1, 1, 1), dim3(kThreads), s, a);
     }
-    if (d->B > 0 || (state && scores)) hipLaunchKernelGGL(score_finish, dim3(1), dim3(kFinishThreads), 0, s, a);
     return launch_status();
 }

@@ -221,13 +221,15 @@ def config_lens(cfg: int, seed: int, *, N: Optional[int] = None, tail=None) -> n
 
 def make_workload(cfg: int, *, kv: bool = True, poison: bool = False, permute: bool = True,
                   N: Optional[int] = None, tail=None, seed: Optional[int] = None,
-                  full_maxb: bool = True) -> Workload:
+                  full_maxb: bool = True, heads=None, head_dim: Optional[int] = None) -> Workload:
     """Build config `cfg` (1..5).  kv=False leaves k_pages/v_pages None (large pools are drawn on
-    the device by the caller).  N / tail shrink a config for fast CPU tests, same structure."""
+    the device by the caller).  N / tail shrink a config for fast CPU tests, same structure;
+    heads = (Hq, Hkv) / head_dim put another head shape on the config's lengths and layout."""
     c = _CFG[cfg]
     seed = (0x5EED0000 + cfg) if seed is None else seed
     Nn = c["N"] if N is None else N
-    shape = AttnShape(Nn, c["Hq"], c["Hkv"], c["D"])
+    Hq, Hkv = heads if heads is not None else (c["Hq"], c["Hkv"])
+    shape = AttnShape(Nn, Hq, Hkv, head_dim if head_dim is not None else c["D"])
     lens = config_lens(cfg, seed, N=Nn, tail=tail)
     P = shape.P
     maxb = None

@@ -21,7 +21,7 @@ def test_header_declares_the_three_calls():
     names = declared_functions()
     for n in ("paged_decode_attn", "step_score", "prune_free", "step_attn_workspace_bytes",
               "step_score_workspace_bytes", "step_prune_workspace_bytes", "step_strerror", "step_version",
-              "step_calib_copy", "step_attn_profile_begin", "step_attn_profile_end",
+              "step_calib_copy", "step_profile_begin", "step_profile_end", "step_profile_kernel_name", "step_read_probe",
               "step_attn_waves_per_head", "step_attn_plan", "paged_decode_attn_planned",
               "step_reserve_workspace_bytes", "step_reserve_pages", "step_append_kv", "step_weighted_vote",
               "prune_free_static", "step_prune_static_max_pages"):
