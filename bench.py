@@ -232,7 +232,7 @@ def main():
         pruned_l = torch.empty(s.N, dtype=torch.int32, device=dev)
         n_pruned_l = torch.zeros(1, dtype=torch.int32, device=dev)
         new_pages_l = torch.empty(s.N, dtype=torch.int32, device=dev)
-        ws_res = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(s.N, bt_np.shape[1], lay.NP)), dev)
+        ws_res = binding.reserve_workspace(rc_l, s.N, bt_np.shape[1])   # the free list is built once, then kept up
         live_at_start = int((lay.seq_lens > 0).sum())
         adims = binding.attn_dims(q, k_pages, bt_l)
         ws_attn = binding.new_workspace(binding.attn_workspace_bytes(adims), dev)

@@ -42,7 +42,8 @@ enum step_error {
     STEP_ENAN = 19,      /* device: NaN score on a live trace                                    */
     STEP_EREFCOUNT = 20, /* device: a released page had refcount <= 0                            */
     STEP_EKLIVE = 21,    /* device: k larger than the number of live traces                      */
-    STEP_EPLAN = 22      /* device: the workspace holds no plan made for these dims              */
+    STEP_EPLAN = 22,     /* device: the workspace holds no plan made for these dims              */
+    STEP_EFREELIST = 23  /* device: no free list in the workspace, or it disagrees with refcounts */
 };
 
 /* Human-readable name of an error code (host pointer to a static string). */
@@ -214,6 +215,21 @@ int prune_free_static(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const floa
 size_t step_reserve_workspace_bytes(int32_t N, int32_t MAXB, int32_t NP);
 
 /*
+ * The free pages of the pool are kept, from call to call, as a bitmap and a count in the workspace of
+ * step_reserve_pages (a page is free when its reference count is 0; that remains the definition).
+ *   step_freelist_rebuild  makes the free list from refcounts [NP]; call it once after the workspace has
+ *                          been allocated and again whenever refcounts changed other than through
+ *                          step_reserve_pages or step_freelist_add.
+ *   step_freelist_add      enters the pages that a prune_free call reports as freed: freed_pages
+ *                          [capacity], *n_freed (device) of them (STEP_EPAGE for an id outside the pool).
+ * A call on a workspace that holds no free list for a pool of NP pages reports STEP_EFREELIST and changes
+ * nothing.  Both calls need workspace >= step_reserve_workspace_bytes(0, 0, NP).
+ */
+int step_freelist_rebuild(int32_t NP, const int32_t *refcounts, void *workspace, size_t workspace_bytes, void *stream);
+int step_freelist_add(int32_t NP, const int32_t *freed_pages, const int32_t *n_freed, int32_t capacity,
+                      void *workspace, size_t workspace_bytes, int32_t *status, void *stream);
+
+/*
  * Before the next decode step: a live trace with seq_lens[i] % P == 0 needs a new page for its next
  * token.  While fewer pages are free (refcount 0) than traces need one, the live trace with the
  * smallest (scores[i], i) is pruned exactly as prune_free prunes one trace (pages released, row set
@@ -221,13 +237,16 @@ size_t step_reserve_workspace_bytes(int32_t N, int32_t MAXB, int32_t NP);
  * read as "the pool cannot hold the pages the next decode step opens".  Then every trace that
  * still needs a page, in ascending index, takes the smallest free page id:
  * block_tables[i][seq_lens[i] / P] = page, refcounts[page] = 1, new_pages[i] = page.
+ * The free pages are read from, and kept up to date in, the free list of the workspace (above): a step
+ * that prunes nothing costs a scan of NP / 32 bitmap words, and none at all when no trace needs a page.
  *
  *   scores [N] fp32 | refcounts [NP], block_tables [N][MAXB], seq_lens [N] int32 in/out
  *   pruned [N] int32 out (first *n_pruned entries, pruning order) | n_pruned [1] int32 out
  *   new_pages [N] int32 out (-1 where no page was given) | workspace >= step_reserve_workspace_bytes
- * Device-reported errors: STEP_ELEN (bad length, or a trace on a page boundary whose row is full),
- * STEP_ENAN (pruning needed and a live score is NaN) -- both before anything is modified;
- * STEP_EPAGE / STEP_EREFCOUNT while releasing (that entry is skipped).  N <= 4096.
+ * Device-reported errors: STEP_EFREELIST (no free list in the workspace: nothing is modified; or a page the
+ * list calls free has a non-zero reference count: that page is skipped), STEP_ELEN (bad length, or a trace
+ * on a page boundary whose row is full), STEP_ENAN (pruning needed and a live score is NaN) -- both before
+ * anything is modified; STEP_EPAGE / STEP_EREFCOUNT while releasing (that entry is skipped).  N <= 4096.
  */
 int step_reserve_pages(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores,
                        int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,

@@ -18,6 +18,7 @@ STEP_OK = 0
 ERROR_NAMES = {
     0: "STEP_OK", 1: "STEP_EINVAL", 2: "STEP_EWORKSPACE", 3: "STEP_ELAUNCH", 16: "STEP_EPAGE",
     17: "STEP_ELEN", 18: "STEP_EINDEX", 19: "STEP_ENAN", 20: "STEP_EREFCOUNT", 21: "STEP_EKLIVE", 22: "STEP_EPLAN",
+    23: "STEP_EFREELIST",
 }
 ACT_RELU, ACT_GELU = 0, 1
 
@@ -75,6 +76,10 @@ def lib():
     L.prune_free_static.argtypes = [i32, i32, i32, i32, vp, i32] + [vp] * 6 + [vp, vp]
     L.step_reserve_workspace_bytes.restype = sz
     L.step_reserve_workspace_bytes.argtypes = [i32, i32, i32]
+    L.step_freelist_rebuild.restype = ctypes.c_int
+    L.step_freelist_rebuild.argtypes = [i32, vp, vp, sz, vp]
+    L.step_freelist_add.restype = ctypes.c_int
+    L.step_freelist_add.argtypes = [i32, vp, vp, i32, vp, sz, vp, vp]
     L.step_reserve_pages.restype = ctypes.c_int
     L.step_reserve_pages.argtypes = [i32, i32, i32, i32] + [vp] * 8 + [sz, vp, vp]
     L.step_append_kv.restype = ctypes.c_int
@@ -258,9 +263,36 @@ def prune_free_static(scores, k, refcounts, block_tables, seq_lens, pruned, free
     return pruned, freed_pages, n_freed
 
 
+def reserve_workspace(refcounts, N=0, MAXB=0):
+    """A workspace for reserve_pages with the free list of `refcounts` built in it."""
+    ws = new_workspace(int(lib().step_reserve_workspace_bytes(N, MAXB, refcounts.numel())), refcounts.device)
+    freelist_rebuild(refcounts, ws)
+    return ws
+
+
+def freelist_rebuild(refcounts, workspace):
+    """(Re)build the free list of the reserve workspace from the reference counts."""
+    rc = lib().step_freelist_rebuild(refcounts.numel(), _dev(refcounts, (torch.int32,), "refcounts"),
+                                     _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "step_freelist_rebuild")
+
+
+def freelist_add(NP, freed_pages, n_freed, workspace, status=None):
+    """Enter the pages a prune_free call freed into the free list of the reserve workspace."""
+    i32 = (torch.int32,)
+    rc = lib().step_freelist_add(int(NP), _dev(freed_pages, i32, "freed_pages"), _dev(n_freed, i32, "n_freed"),
+                                 freed_pages.numel(), _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(),
+                                 _dev(status, i32, "status", True), _stream())
+    if rc != STEP_OK:
+        raise StepError(rc, "step_freelist_add")
+
+
 def reserve_pages(scores, refcounts, block_tables, seq_lens, pruned=None, n_pruned=None, new_pages=None,
                   workspace=None, status=None, P=16):
-    """Memory-triggered pruning + allocation in place; returns (pruned [N], n_pruned [1], new_pages [N])."""
+    """Memory-triggered pruning + allocation in place; returns (pruned [N], n_pruned [1], new_pages [N]).
+    `workspace` holds the free list from call to call (reserve_workspace); without one a fresh free list is
+    built from refcounts for this call."""
     N, MAXB = block_tables.shape
     NP = refcounts.numel()
     dev = scores.device
@@ -272,7 +304,7 @@ def reserve_pages(scores, refcounts, block_tables, seq_lens, pruned=None, n_prun
     if new_pages is None:
         new_pages = torch.empty(max(N, 1), dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = new_workspace(int(lib().step_reserve_workspace_bytes(N, MAXB, NP)), dev)
+        workspace = reserve_workspace(refcounts, N, MAXB)
     rc = lib().step_reserve_pages(
         N, MAXB, NP, int(P), _dev(scores, (torch.float32,), "scores"), _dev(refcounts, i32, "refcounts"),
         _dev(block_tables, i32, "block_tables"), _dev(seq_lens, i32, "seq_lens"), _dev(pruned, i32, "pruned"),

@@ -99,9 +99,12 @@ Layout layout_for(const step_attn_dims *d)
     l.prefix_qt = !prefix_enabled() ? 0 : ((long long)d->N * G >= 256) ? 2 : 1;
     l.TB = 16 * (l.prefix_qt ? l.prefix_qt : 1) / G;
     l.nblk = (d->N + l.TB - 1) / l.TB;
-    // sub-chunks of a shared prefix per trace: N * pmax <= 4 Wh + N partial slots
-    l.pmax = 1 + 4 * l.Wh / (d->N > 0 ? d->N : 1);
+    // sub-chunks of a shared prefix per trace: never more than prefix_split can ask for (about one wave per
+    // SIMD over the blocks of a KV head), at most kMaxParts, and N * pmax <= 4096 partial slots
+    l.pmax = 4096 / (d->N > 0 ? d->N : 1);
     if (l.pmax > kMaxParts) l.pmax = kMaxParts;
+    if (l.nblk > 0 && l.pmax > (l.Wh + l.nblk - 1) / l.nblk) l.pmax = (l.Wh + l.nblk - 1) / l.nblk;
+    if (l.pmax < 1) l.pmax = 1;
     l.max_slots = d->N * l.pmax + d->N + l.Wh;  // private pages: at most one record per trace and one more per wave
     const size_t R = (size_t)l.max_slots, N = d->N;
     l.blk_shared = 256;

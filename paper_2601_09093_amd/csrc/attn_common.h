@@ -88,57 +88,109 @@ __device__ __forceinline__ int pages_of(int L, int MAXB)
     return (L > 0 && (long long)L <= (long long)MAXB * kPageTokens) ? (L + kPageTokens - 1) / kPageTokens : 0;
 }
 
-// Live traces of block b (bit r: trace b * TB + r has pages) and the fewest full pages among them.
-// Every lane of the wave calls; the results are wave-uniform.
-__device__ __forceinline__ unsigned block_live(const AttnArgs &a, int b, int lane, int &minfull)
+// What one wave finds out about block b of the traces.
+struct BlockPrefix {
+    unsigned live;     // bit r: trace b * TB + r has pages
+    int S;             // S_b: leading block-table entries common to every live trace of the block, below each
+                       // one's last full page, at most kMaxShared (0 with fewer than two live traces)
+    bool have_ids;     // ids_a / ids_b are valid
+    int ids_a, ids_b;  // per lane: entries `lane` and `64 + lane` of the first live trace's row (exact below S_b)
+};
+
+// Every lane of the wave calls; the results are wave-uniform (ids_a / ids_b are per lane).  detect = false only
+// looks at the lengths (S comes back 0).  The search takes 128 columns per trip with the loads of up to 8 rows
+// in flight together; for a block of at most 8 traces the first trip's loads are requested together with the
+// lengths (columns clamped to the row, compared only below the cap the lengths give).
+__device__ __forceinline__ BlockPrefix block_prefix(const AttnArgs &a, int b, int lane, bool detect)
 {
+    BlockPrefix r;
+    r.S = 0;
+    r.have_ids = false;
+    r.ids_a = r.ids_b = 0;
     const int t0 = b * a.TB, nt = min(a.TB, a.N - t0);
+    const int32_t *rows = a.block_tables + (size_t)t0 * a.MAXB;
+    const bool spec = detect && nt <= 8 && a.MAXB > 0;
     int L = 0;
     if (lane < nt) L = a.seq_lens[t0 + lane];
+    int xa[8], xb[8];
+    if (spec) {
+        const int ca = min(lane, a.MAXB - 1), cb = min(64 + lane, a.MAXB - 1);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int rr = min(u, nt - 1);
+            xa[u] = rows[(size_t)rr * a.MAXB + ca];
+            xb[u] = rows[(size_t)rr * a.MAXB + cb];
+        }
+    }
     const bool ok = pages_of(L, a.MAXB) > 0;
     int mf = ok ? L / kPageTokens : 0x7fffffff;
 #pragma unroll
     for (int off = 16; off >= 1; off >>= 1) mf = min(mf, __shfl_xor(mf, off));
-    minfull = __builtin_amdgcn_readfirstlane(mf);
-    return (unsigned)__ballot(ok);
-}
-
-// S_b: leading block-table entries common to every live trace of block b, below each one's last full
-// page, at most kMaxShared.  128 columns per trip, the loads of up to 8 rows in flight together.
-__device__ __forceinline__ int block_shared_pages(const AttnArgs &a, int b, int lane, unsigned live, int minfull)
-{
-    if (__popc(live) < 2) return 0;
+    const int minfull = __builtin_amdgcn_readfirstlane(mf);
+    const unsigned live = (unsigned)__ballot(ok);
+    r.live = live;
+    if (!detect || __popc(live) < 2) return r;
     const int cap = min(min(kMaxShared, minfull), a.MAXB);
-    if (cap <= 0) return 0;
-    const int t0 = b * a.TB, nt = min(a.TB, a.N - t0);
+    if (cap <= 0) return r;
     const int f = __ffs(live) - 1;
-    const int32_t *rows = a.block_tables + (size_t)t0 * a.MAXB;
     const int32_t *row_f = rows + (size_t)f * a.MAXB;
     for (int c0 = 0; c0 < cap; c0 += 128) {
-        const int ca = min(c0 + lane, cap - 1), cb = min(c0 + 64 + lane, cap - 1);  // clamped: a repeat of the last column
-        const int ref_a = row_f[ca], ref_b = row_f[cb];
+        int ref_a, ref_b;
         bool diff_a = false, diff_b = false;
-        for (int r0 = 0; r0 < nt; r0 += 8) {
-            int xa[8], xb[8];
+        if (c0 == 0 && spec) {
+            ref_a = xa[0];
+            ref_b = xb[0];
+#pragma unroll
+            for (int u = 1; u < 8; ++u)
+                if (f == u) {
+                    ref_a = xa[u];
+                    ref_b = xb[u];
+                }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int r = min(r0 + u, nt - 1);
-                xa[u] = rows[(size_t)r * a.MAXB + ca];
-                xb[u] = rows[(size_t)r * a.MAXB + cb];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int r = min(r0 + u, nt - 1);
-                const bool is_live = (live >> r) & 1u;
+                const bool is_live = (live >> min(u, nt - 1)) & 1u;
                 diff_a |= is_live && xa[u] != ref_a;
                 diff_b |= is_live && xb[u] != ref_b;
             }
+            diff_a &= lane < cap;
+            diff_b &= 64 + lane < cap;
+        } else {
+            const int ca = min(c0 + lane, cap - 1), cb = min(c0 + 64 + lane, cap - 1);  // clamped: a repeat of the last column
+            ref_a = row_f[ca];
+            ref_b = row_f[cb];
+            for (int r0 = 0; r0 < nt; r0 += 8) {
+                int ya[8], yb[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int rr = min(r0 + u, nt - 1);
+                    ya[u] = rows[(size_t)rr * a.MAXB + ca];
+                    yb[u] = rows[(size_t)rr * a.MAXB + cb];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool is_live = (live >> min(r0 + u, nt - 1)) & 1u;
+                    diff_a |= is_live && ya[u] != ref_a;
+                    diff_b |= is_live && yb[u] != ref_b;
+                }
+            }
+        }
+        if (c0 == 0) {
+            r.have_ids = true;
+            r.ids_a = ref_a;
+            r.ids_b = ref_b;
         }
         const unsigned long long da = __ballot(diff_a), db = __ballot(diff_b);
-        if (da) return min(cap, c0 + (int)__ffsll(da) - 1);
-        if (db) return min(cap, c0 + 64 + (int)__ffsll(db) - 1);
+        if (da) {
+            r.S = min(cap, c0 + (int)__ffsll(da) - 1);
+            return r;
+        }
+        if (db) {
+            r.S = min(cap, c0 + 64 + (int)__ffsll(db) - 1);
+            return r;
+        }
     }
-    return cap;
+    r.S = cap;
+    return r;
 }
 
 // Sub-chunks of a shared prefix of S pages: about one wave per SIMD over the blocks of a KV head, whole page

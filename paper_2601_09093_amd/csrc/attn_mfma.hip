@@ -159,11 +159,24 @@ __global__ __launch_bounds__(64) void attn_front(const AttnArgs a)
     const int b = u % a.nblk, p = u / a.nblk;
     const int t0 = b * a.TB;
 
-    int minfull;
-    const unsigned live = block_live(a, b, lane, minfull);
-    int S;
+    // query rows of this block: row = (trace - t0) * G + head-in-group.  Requested first (they depend on nothing
+    // the wave still has to find out; rows of dead traces are zeroed below)
+    uint4 qf[QT][KB];
+    int trace_of[QT], hh_of[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int row = qt * 16 + c;
+        trace_of[qt] = min(t0 + row / G, a.N - 1);
+        hh_of[qt] = row % G;
+        const uint16_t *qrow = a.q + ((size_t)trace_of[qt] * a.Hq + g * G + hh_of[qt]) * D;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) qf[qt][kb] = *reinterpret_cast<const uint4 *>(qrow + kb * 32 + gr * 8);
+    }
+
+    const BlockPrefix bp = block_prefix(a, b, lane, DETECT);
+    const unsigned live = bp.live;
+    int S = bp.S;
     if constexpr (DETECT) {
-        S = block_shared_pages(a, b, lane, live, minfull);
         if (p == 0 && g == 0 && lane == 0) {
             a.blk_shared[b] = S;
             if (b == 0) a.hdr->stamp = a.stamp;
@@ -172,6 +185,8 @@ __global__ __launch_bounds__(64) void attn_front(const AttnArgs a)
         // lengths made for other dims (or none at all) are reported; the clamp keeps every access inside
         // the block tables whatever the workspace holds
         if (a.hdr->stamp != a.stamp && lane == 0) report(a.status, STEP_EPLAN);
+        int minfull = 0x7fffffff;
+        for (unsigned m = live; m; m &= m - 1) minfull = min(minfull, scalar_read(a.seq_lens + t0 + __ffs(m) - 1) / kPageTokens);
         S = __popc(live) >= 2 ? min(max(scalar_read(a.blk_shared + b), 0), min(min(kMaxShared, minfull), a.MAXB)) : 0;
     }
     int parts, sc;
@@ -185,30 +200,27 @@ __global__ __launch_bounds__(64) void attn_front(const AttnArgs a)
     }
 
     bool bad_page = false;
-    const int32_t *bt = a.block_tables + (size_t)(t0 + __ffs(live) - 1) * a.MAXB + first;  // first + n <= S <= MAXB
+    const int32_t *bt = a.block_tables + (size_t)(t0 + __ffs(live) - 1) * a.MAXB;  // first + n <= S <= MAXB
     auto page_at = [&](int j) {
-        const int pg = scalar_read(bt + min(j, n - 1));  // the same for every lane
+        const int col = first + min(j, n - 1);  // the same for every lane
+        int pg;
+        if (bp.have_ids && col < 128)  // the search has already fetched the row's first 128 entries
+            pg = col < 64 ? __builtin_amdgcn_readlane(bp.ids_a, col) : __builtin_amdgcn_readlane(bp.ids_b, col - 64);
+        else
+            pg = scalar_read(bt + col);
         const bool ok = (u32)pg < (u32)a.NP;
         bad_page |= !ok;
         return ok ? pg : 0;
     };
 
-    // query rows of this block: row = (trace - t0) * G + head-in-group
-    uint4 qf[QT][KB];
-    int trace_of[QT], hh_of[QT];
     bool valid[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        const int row = qt * 16 + c;
-        const int r = row / G;
+        const int r = (qt * 16 + c) / G;
         valid[qt] = r < a.TB && ((live >> r) & 1u);
-        trace_of[qt] = valid[qt] ? t0 + r : t0 + __ffs(live) - 1;
-        hh_of[qt] = row % G;
-        const uint16_t *qrow = a.q + ((size_t)trace_of[qt] * a.Hq + g * G + hh_of[qt]) * D;
+        if (!valid[qt]) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(qrow + kb * 32 + gr * 8);
-            qf[qt][kb] = valid[qt] ? x : make_uint4(0, 0, 0, 0);
+            for (int kb = 0; kb < KB; ++kb) qf[qt][kb] = make_uint4(0, 0, 0, 0);
         }
     }
 
@@ -288,11 +300,10 @@ __global__ __launch_bounds__(64) void attn_plan_blocks(const AttnArgs a)
 {
     const int lane = threadIdx.x, b = blockIdx.x;
     const int t0 = b * a.TB, nt = min(a.TB, a.N - t0);
-    int minfull;
-    const unsigned live = block_live(a, b, lane, minfull);
+    const BlockPrefix bp = block_prefix(a, b, lane, a.prefix_qt != 0);
     const int L = lane < nt ? a.seq_lens[t0 + lane] : 0;
     if (__any(L != 0 && pages_of(L, a.MAXB) == 0) && lane == 0) report(a.status, STEP_ELEN);
-    const int S = a.prefix_qt ? block_shared_pages(a, b, lane, live, minfull) : 0;
+    const int S = bp.S;
     if (lane == 0) {
         a.blk_shared[b] = S;
         if (b == 0) a.hdr->stamp = a.stamp;

@@ -98,7 +98,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int *scratch /*[32]*/, int
 // ---------------------------------------------------------------------------------------------
 enum KernelId {
     kKernFront = 0, kKernPlanBlocks, kKernStage1, kKernMerge, kKernScore, kKernScoreFinish, kKernPruneFused,
-    kKernPruneSelect, kKernPruneRelease, kKernPruneCompact, kKernReserve, kKernAppend, kKernVote, kKernCopy,
+    kKernPruneSelect, kKernPruneRelease, kKernPruneCompact, kKernReserve, kKernFreelist, kKernAppend, kKernVote, kKernCopy,
     kKernReadProbe, kKernCount
 };
 

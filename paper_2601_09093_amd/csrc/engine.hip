@@ -7,7 +7,11 @@
 //                       with the lowest score is pruned and its pages released (Algorithm 1:
 //                       argmin, ReleaseKVCache, T <- T \ {t*}), one trace at a time.  Then every
 //                       trace that still needs a page, in ascending index, takes the smallest free
-//                       page id.
+//                       page id.  The free pages are kept as a bitmap (and a count) in the workspace from
+//                       call to call: releasing sets bits, allocating clears them, so a step costs a scan
+//                       of NP / 32 words instead of NP reference counts.  step_freelist_rebuild makes the
+//                       bitmap from the reference counts (the definition of "free"), step_freelist_add
+//                       enters the pages a prune_free call has freed.
 //   step_append_kv      the KV-cache write of NextToken(t): row L_i of every live trace, L_i += 1.
 //   step_weighted_vote  WeightedVote of Algorithm 1 / Section 4.3: the answer whose traces' final
 //                       scores sum highest.
@@ -36,12 +40,97 @@ __device__ int block_sum(int v, int *scratch /*[17]*/)
     return t;
 }
 
+struct FreeListHeader {  // first 256 bytes of the reserve workspace
+    int32_t stamp;        // freelist_stamp(NP) once the bitmap has been built for a pool of NP pages
+    int32_t nfree;        // set bits of the bitmap
+    int32_t pad[62];
+};
+
+__host__ __device__ inline int32_t freelist_stamp(int NP) { return (int32_t)((0x46524545u ^ ((u32)NP * 2654435761u)) | 1u); }
+
 struct ReserveArgs {
     const float *scores;
     int32_t *refcounts, *block_tables, *seq_lens, *pruned, *n_pruned, *new_pages, *status;
+    FreeListHeader *hdr;
     u32 *bitmap;  // ceil(NP / 64) * 2 words: bit p set <=> page p is free
-    int N, MAXB, NP, P, words;
+    const int32_t *freed_pages, *n_freed;  // step_freelist_add only
+    int N, MAXB, NP, P, words, cap;
 };
+
+// step_freelist_rebuild: bit p of the bitmap = (refcounts[p] == 0), count of set bits, stamp.  One workgroup;
+// all loads of a thread are issued before the first is used (four pages per 16-byte load, 16 loads in flight),
+// eight neighbouring lanes then assemble one 32-bit word of the bitmap.
+__global__ __launch_bounds__(kThreads) void freelist_rebuild_kernel(const ReserveArgs a)
+{
+    __shared__ int scratch[32];
+    const int tid = threadIdx.x, lane = tid & 63;
+    int my_free = 0;
+    constexpr int kBatch = 16;
+    const int quads = a.words * 8;  // groups of four pages
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(a.refcounts) & 15) == 0;
+    for (int base = 0; base < quads; base += kBatch * kThreads) {
+        int4 v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int qd = base + u * kThreads + tid;
+            const int p = qd * 4;
+            v[u] = make_int4(1, 1, 1, 1);
+            if (qd < quads) {
+                if (vec_ok && p + 3 < a.NP) {
+                    v[u] = *reinterpret_cast<const int4 *>(a.refcounts + p);
+                } else {
+                    if (p + 0 < a.NP) v[u].x = a.refcounts[p + 0];
+                    if (p + 1 < a.NP) v[u].y = a.refcounts[p + 1];
+                    if (p + 2 < a.NP) v[u].z = a.refcounts[p + 2];
+                    if (p + 3 < a.NP) v[u].w = a.refcounts[p + 3];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int qd = base + u * kThreads + tid;
+            u32 nib = (v[u].x == 0 ? 1u : 0u) | (v[u].y == 0 ? 2u : 0u) | (v[u].z == 0 ? 4u : 0u) |
+                      (v[u].w == 0 ? 8u : 0u);
+            u32 word = nib << (4 * (lane & 7));
+            word |= __shfl_xor(word, 1);
+            word |= __shfl_xor(word, 2);
+            word |= __shfl_xor(word, 4);
+            if ((lane & 7) == 0 && qd < quads) {
+                a.bitmap[qd >> 3] = word;
+                my_free += __popc(word);
+            }
+        }
+    }
+    const int nfree = block_sum(my_free, scratch);
+    if (tid == 0) {
+        a.hdr->nfree = nfree;
+        a.hdr->stamp = freelist_stamp(a.NP);
+    }
+}
+
+// step_freelist_add: the pages of a freed list (what prune_free reports) become free in the bitmap
+__global__ __launch_bounds__(kThreads) void freelist_add_kernel(const ReserveArgs a)
+{
+    __shared__ int scratch[32];
+    const int tid = threadIdx.x;
+    if (a.hdr->stamp != freelist_stamp(a.NP)) {
+        if (tid == 0) report(a.status, STEP_EFREELIST);
+        return;
+    }
+    const int n = min(max(*a.n_freed, 0), a.cap);
+    int added = 0;
+    for (int i = tid; i < n; i += kThreads) {
+        const int p = a.freed_pages[i];
+        if ((u32)p >= (u32)a.NP) {
+            report(a.status, STEP_EPAGE);
+            continue;
+        }
+        const u32 bit = 1u << (p & 31);
+        if (!(atomicOr(&a.bitmap[p >> 5], bit) & bit)) ++added;
+    }
+    added = block_sum(added, scratch);
+    if (tid == 0) a.hdr->nfree += added;
+}
 
 __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveArgs a)
 {
@@ -53,6 +142,13 @@ __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveAr
     const int tid = threadIdx.x, lane = tid & 63;
     if (tid == 0) err_s = 0;
     __syncthreads();
+    if (a.hdr->stamp != freelist_stamp(a.NP)) {  // no free list was built for this pool in this workspace
+        if (tid == 0) {
+            report(a.status, STEP_EFREELIST);
+            *a.n_pruned = 0;
+        }
+        return;
+    }
 
     // lengths, traces on a page boundary
     int my_need = 0;
@@ -69,51 +165,8 @@ __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveAr
         lens[i] = keep;
         a.new_pages[i] = -1;
     }
-    // free-page bitmap from the refcounts.  The scan runs right after the attention kernel has
-    // streamed gigabytes through every cache, so each dependent round trip is a cold one: all loads
-    // of a thread are issued before the first is used (four pages per 16-byte load, 16 loads
-    // in flight), eight neighbouring lanes then assemble one 32-bit word of the bitmap.
-    int my_free = 0;
-    {
-        constexpr int kBatch = 16;
-        const int quads = a.words * 8;  // groups of four pages
-        const bool vec_ok = (reinterpret_cast<uintptr_t>(a.refcounts) & 15) == 0;
-        for (int base = 0; base < quads; base += kBatch * kThreads) {
-            int4 v[kBatch];
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int qd = base + u * kThreads + tid;
-                const int p = qd * 4;
-                v[u] = make_int4(1, 1, 1, 1);
-                if (qd < quads) {
-                    if (vec_ok && p + 3 < a.NP) {
-                        v[u] = *reinterpret_cast<const int4 *>(a.refcounts + p);
-                    } else {
-                        if (p + 0 < a.NP) v[u].x = a.refcounts[p + 0];
-                        if (p + 1 < a.NP) v[u].y = a.refcounts[p + 1];
-                        if (p + 2 < a.NP) v[u].z = a.refcounts[p + 2];
-                        if (p + 3 < a.NP) v[u].w = a.refcounts[p + 3];
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int qd = base + u * kThreads + tid;
-                u32 nib = (v[u].x == 0 ? 1u : 0u) | (v[u].y == 0 ? 2u : 0u) | (v[u].z == 0 ? 4u : 0u) |
-                          (v[u].w == 0 ? 8u : 0u);
-                u32 word = nib << (4 * (lane & 7));
-                word |= __shfl_xor(word, 1);
-                word |= __shfl_xor(word, 2);
-                word |= __shfl_xor(word, 4);
-                if ((lane & 7) == 0 && qd < quads) {
-                    a.bitmap[qd >> 3] = word;
-                    my_free += __popc(word);
-                }
-            }
-        }
-    }
     int needed = block_sum(my_need, scratch);
-    int nfree = block_sum(my_free, scratch);
+    int nfree = a.hdr->nfree;
     __syncthreads();
     if (err_s == 0 && nfree < needed) {  // pruning will happen: every live score must be a number
         for (int i = tid; i < a.N; i += kThreads)
@@ -170,8 +223,8 @@ __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveAr
                         atomicAdd(&a.refcounts[p], 1);
                         report(a.status, STEP_EREFCOUNT);
                     } else if (old == 1) {
-                        atomicOr(&a.bitmap[p >> 5], 1u << (p & 31));
-                        ++my_freed;
+                        const u32 bit = 1u << (p & 31);
+                        if (!(atomicOr(&a.bitmap[p >> 5], bit) & bit)) ++my_freed;
                     }
                 }
             }
@@ -202,6 +255,10 @@ __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveAr
         total_need += tot;
     }
     __syncthreads();
+    if (total_need == 0) {  // nothing to hand out: the bitmap is not even looked at
+        if (tid == 0) a.hdr->nfree = nfree;
+        return;
+    }
     // free pages in ascending id: thread owns a contiguous range of bitmap words
     const int per = (a.words + kThreads - 1) / kThreads;
     const int w0 = min(tid * per, a.words), w1 = min(w0 + per, a.words);
@@ -209,19 +266,33 @@ __global__ __launch_bounds__(kThreads) void reserve_pages_kernel(const ReserveAr
     for (int wv = w0; wv < w1; ++wv) cnt += __popc(__atomic_load_n(&a.bitmap[wv], __ATOMIC_RELAXED));
     int total_free;
     int pos = block_excl_scan(cnt, scratch, &total_free);
+    int taken = 0;
     if (cnt > 0 && pos < total_need)
         for (int wv = w0; wv < w1 && pos < total_need; ++wv) {
             u32 bits = __atomic_load_n(&a.bitmap[wv], __ATOMIC_RELAXED);
+            u32 used = 0;
             while (bits && pos < total_need) {
                 const int b = __ffs(bits) - 1;
                 bits &= bits - 1;
                 const int page = wv * 32 + b;
                 const int i = need_list[pos++];
+                used |= 1u << b;
+                if (page >= a.NP || a.refcounts[page] != 0) {  // the bitmap does not match the reference counts
+                    report(a.status, STEP_EFREELIST);
+                    continue;
+                }
                 a.block_tables[(size_t)i * a.MAXB + lens[i] / a.P] = page;
                 a.refcounts[page] = 1;
                 a.new_pages[i] = page;
+                ++taken;
             }
+            if (used) a.bitmap[wv] &= ~used;  // this thread owns the word
         }
+    taken = block_sum(taken, scratch);
+    if (tid == 0) {
+        if (total_free != nfree) report(a.status, STEP_EFREELIST);  // the count and the bitmap have come apart
+        a.hdr->nfree = total_free - min(total_need, total_free);
+    }
 }
 
 struct AppendArgs {
@@ -333,6 +404,41 @@ extern "C" size_t step_reserve_workspace_bytes(int32_t N, int32_t MAXB, int32_t 
     return ((words * sizeof(u32) + 255) & ~(size_t)255) + 256;
 }
 
+namespace {
+bool freelist_args(ReserveArgs &a, int32_t NP, void *workspace, size_t workspace_bytes)
+{
+    if (NP < 0) return false;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < step_reserve_workspace_bytes(0, 0, NP)) return false;
+    a.hdr = reinterpret_cast<FreeListHeader *>(workspace);
+    a.bitmap = reinterpret_cast<u32 *>(reinterpret_cast<char *>(workspace) + 256);
+    a.NP = NP;
+    a.words = (int)((((size_t)NP + 63) / 64) * 2);
+    return true;
+}
+}  // namespace
+
+extern "C" int step_freelist_rebuild(int32_t NP, const int32_t *refcounts, void *workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    if (NP < 0 || (NP > 0 && !refcounts)) return STEP_EINVAL;
+    ReserveArgs a = {};
+    if (!freelist_args(a, NP, workspace, workspace_bytes)) return STEP_EWORKSPACE;
+    a.refcounts = const_cast<int32_t *>(refcounts);
+    launch_kernel(kKernFreelist, freelist_rebuild_kernel, dim3(1), dim3(kThreads), reinterpret_cast<hipStream_t>(stream), a);
+    return launch_status();
+}
+
+extern "C" int step_freelist_add(int32_t NP, const int32_t *freed_pages, const int32_t *n_freed, int32_t capacity,
+                                 void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
+{
+    if (NP < 0 || capacity < 0 || !n_freed || (capacity > 0 && !freed_pages)) return STEP_EINVAL;
+    ReserveArgs a = {};
+    if (!freelist_args(a, NP, workspace, workspace_bytes)) return STEP_EWORKSPACE;
+    a.freed_pages = freed_pages; a.n_freed = n_freed; a.cap = capacity; a.status = status;
+    launch_kernel(kKernFreelist, freelist_add_kernel, dim3(1), dim3(kThreads), reinterpret_cast<hipStream_t>(stream), a);
+    return launch_status();
+}
+
 extern "C" int step_reserve_pages(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *scores,
                                   int32_t *refcounts, int32_t *block_tables, int32_t *seq_lens, int32_t *pruned,
                                   int32_t *n_pruned, int32_t *new_pages, void *workspace, size_t workspace_bytes,
@@ -341,14 +447,11 @@ extern "C" int step_reserve_pages(int32_t N, int32_t MAXB, int32_t NP, int32_t P
     if (N < 0 || N > kMaxN || MAXB < 0 || NP < 0 || P <= 0) return STEP_EINVAL;
     if (!n_pruned) return STEP_EINVAL;
     if (N > 0 && (!scores || !seq_lens || !block_tables || !refcounts || !pruned || !new_pages)) return STEP_EINVAL;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < step_reserve_workspace_bytes(N, MAXB, NP))
-        return STEP_EWORKSPACE;
-    ReserveArgs a;
+    ReserveArgs a = {};
+    if (!freelist_args(a, NP, workspace, workspace_bytes)) return STEP_EWORKSPACE;
     a.scores = scores; a.refcounts = refcounts; a.block_tables = block_tables; a.seq_lens = seq_lens;
     a.pruned = pruned; a.n_pruned = n_pruned; a.new_pages = new_pages; a.status = status;
-    a.bitmap = reinterpret_cast<u32 *>(workspace);
-    a.N = N; a.MAXB = MAXB; a.NP = NP; a.P = P;
-    a.words = (int)((((size_t)NP + 63) / 64) * 2);
+    a.N = N; a.MAXB = MAXB; a.P = P;
     launch_kernel(kKernReserve, reserve_pages_kernel, dim3(1), dim3(kThreads), reinterpret_cast<hipStream_t>(stream), a);
     return launch_status();
 }

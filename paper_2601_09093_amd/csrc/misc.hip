@@ -79,6 +79,7 @@ extern "C" const char *step_strerror(int code)
         case STEP_EREFCOUNT: return "STEP_EREFCOUNT: released page had refcount <= 0";
         case STEP_EKLIVE: return "STEP_EKLIVE: k exceeds the number of live traces";
         case STEP_EPLAN: return "STEP_EPLAN: the workspace holds no attention plan made for these dims";
+        case STEP_EFREELIST: return "STEP_EFREELIST: the workspace holds no free list for this pool, or it does not match the refcounts";
     }
     return "unknown libstep error";
 }
@@ -119,7 +120,7 @@ extern "C" const char *step_profile_kernel_name(int id)
 {
     static const char *const names[step::kKernCount] = {
         "attn_front", "attn_plan_blocks", "attn_partial", "attn_merge", "score_hidden", "score_finish", "prune_fused",
-        "prune_select", "prune_release", "prune_compact", "reserve_pages", "append_kv", "weighted_vote", "calib_copy",
+        "prune_select", "prune_release", "prune_compact", "reserve_pages", "freelist", "append_kv", "weighted_vote", "calib_copy",
         "read_probe"};
     return (id >= 0 && id < step::kKernCount) ? names[id] : "unknown";
 }

@@ -24,7 +24,7 @@ def test_header_declares_the_three_calls():
               "step_calib_copy", "step_profile_begin", "step_profile_end", "step_profile_kernel_name", "step_read_probe",
               "step_attn_waves_per_head", "step_attn_plan", "paged_decode_attn_planned",
               "step_reserve_workspace_bytes", "step_reserve_pages", "step_append_kv", "step_weighted_vote",
-              "prune_free_static", "step_prune_static_max_pages"):
+              "prune_free_static", "step_prune_static_max_pages", "step_freelist_rebuild", "step_freelist_add"):
         assert n in names, names
 
 

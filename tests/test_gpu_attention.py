@@ -261,6 +261,48 @@ def test_planner_corner_cases(case):
     check(q, k, v, lay.block_tables, lay.seq_lens)
 
 
+@pytest.mark.parametrize("G,D", [(4, 128), (1, 64), (8, 128), (2, 128)])
+def test_blocks_of_traces_with_different_shared_prefixes(G, D):
+    """Shared prefixes are found per block of 16 * QT / G consecutive traces.  Here groups of traces share
+    different prompts of different lengths (two prompts in one batch), some blocks hold a single live trace or
+    none, one trace ends inside its group's prompt pages, and the groups do not line up with the blocks."""
+    Hkv = 2
+    r = wl.rng_for(4400 + G + D, 0)
+    groups = [(11, 20), (7, 0), (9, 130), (5, 3), (13, 64), (1, 9), (6, 257)]     # (traces, prompt pages)
+    lens, prompts = [], []
+    for n, pp in groups:
+        for _ in range(n):
+            lens.append(pp * P + int(r.integers(0 if pp else 1, 700)))
+            prompts.append(pp)
+    lens = np.array(lens)
+    lens[3] = 0; lens[12] = 0; lens[30:34] = 0
+    lens[20] = 130 * P                                             # ends exactly at its group's prompt
+    N = lens.size
+    nb = (lens + P - 1) // P
+    MAXB = int(nb.max()) + 3
+    bt = np.full((N, MAXB), -1, np.int32)
+    nxt, i0 = 0, 0
+    for n, pp in groups:                                           # prompt pages of a group, then private pages
+        shared = np.arange(nxt, nxt + pp); nxt += pp
+        for i in range(i0, i0 + n):
+            if lens[i] == 0:
+                continue
+            bt[i, :pp] = shared
+            bt[i, pp:nb[i]] = np.arange(nxt, nxt + nb[i] - pp); nxt += nb[i] - pp
+        i0 += n
+    perm = wl.rng_for(4400, 1).permutation(nxt + 17).astype(np.int32)
+    bt = np.where(bt >= 0, perm[np.maximum(bt, 0)], -1).astype(np.int32)
+    NP = nxt + 17
+    sl = lens.astype(np.int32)
+    lay = wl.PagedLayout(sl, bt, np.zeros(NP, np.int32), NP, MAXB, 0, nxt, 0, int(lens.sum()))
+    q = wl.normal_bf16(wl.rng_for(4400, 2), (N, G * Hkv, D))
+    k = wl.normal_bf16(wl.rng_for(4400, 3), (NP, Hkv, P, D))
+    v = wl.normal_bf16(wl.rng_for(4400, 4), (NP, Hkv, P, D))
+    wl.poison_unused(k, v, lay, P)
+    got, _ = check(q, k, v, bt, sl)
+    assert np.all(got[lens == 0] == 0)
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_random_shapes_and_length_mixes(seed):
     """Seeded sweep over head shapes (KV-head counts that do not divide the chip evenly included),

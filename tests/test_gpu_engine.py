@@ -86,6 +86,52 @@ def test_reserve_pages_errors():
     assert np.array_equal(got[2], lay.refcounts) and np.array_equal(got[3], lay.block_tables)
 
 
+def test_free_list_is_kept_across_prune_free_and_reserve_calls():
+    """One workspace through a sequence of calls that free and take pages: reserve (pruning under pressure),
+    prune_free followed by step_freelist_add, reserve again.  After every call the state equals the oracle's
+    (which scans the reference counts every time), and a workspace without a free list is refused."""
+    r = wl.rng_for(1234, 0)
+    N = 24
+    lens = 32 + 16 * r.integers(1, 5, N)                              # every trace sits on a page boundary
+    lay = wl.build_layout(lens, 32, P, wl.rng_for(1234, 1), slack=1.0, maxb=12)
+    NP = lay.NP + 5
+    rc = np.concatenate([lay.refcounts, np.zeros(5, np.int32)])
+    bt, sl = lay.block_tables.copy(), lay.seq_lens.copy()
+    scores = r.random(N).astype(np.float32)
+    t_rc, t_bt, t_sl, t_sc = dev(rc), dev(bt), dev(sl), dev(scores)
+    st = new_status()
+    ws = binding.new_workspace(int(binding.lib().step_reserve_workspace_bytes(N, 12, NP)), DEV)
+    ws.fill_(0x5A)
+    binding.reserve_pages(t_sc, t_rc, t_bt, t_sl, workspace=ws, status=st)
+    torch.cuda.synchronize()
+    assert binding.ERROR_NAMES[int(st.item())] == "STEP_EFREELIST"
+    assert np.array_equal(t_rc.cpu().numpy(), rc) and np.array_equal(t_bt.cpu().numpy(), bt)   # nothing was modified
+    st.zero_()
+    binding.freelist_rebuild(t_rc, ws)
+
+    def same_state():
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0, binding.ERROR_NAMES.get(int(st.item()))
+        assert np.array_equal(t_rc.cpu().numpy(), rc) and np.array_equal(t_bt.cpu().numpy(), bt)
+        assert np.array_equal(t_sl.cpu().numpy(), sl)
+
+    for round_ in range(4):
+        pruned, n_pruned, new_pages = binding.reserve_pages(t_sc, t_rc, t_bt, t_sl, workspace=ws, status=st)
+        o_pruned, o_new = oracle.reserve_pages(scores, rc, bt, sl, P)
+        same_state()
+        assert pruned.cpu().numpy()[: int(n_pruned.item())].tolist() == o_pruned.tolist()
+        assert np.array_equal(new_pages.cpu().numpy()[:N], o_new)
+        live = np.nonzero(sl > 0)[0]
+        sl[live] += 16; t_sl.copy_(dev(sl))                           # the traces fill their new page
+        if round_ == 1:                                               # a fixed-fraction prune in between
+            k = 3
+            pr, fr, nf = binding.prune_free(t_sc, k, t_rc, t_bt, t_sl, status=st)
+            binding.freelist_add(NP, fr, nf, ws, status=st)
+            oracle.prune_free(scores, k, rc, bt, sl, P)
+            same_state()
+    assert (sl > 0).sum() >= 1
+
+
 def test_append_kv_bit_exact():
     lay = wl.build_layout(np.array([17, 32, 0, 5, 100, 48]), 0, P, wl.rng_for(6, 1), slack=1.5, maxb=8)
     Hkv, D = 8, 128
@@ -153,6 +199,7 @@ def _decode_loop(NP):
     t_W1, t_b1, t_W2 = dev_bits(sc.W1), dev(sc.b1), dev_bits(sc.W2)
     t_b2 = torch.tensor([sc.b2], dtype=torch.float32, device=DEV)
     st = new_status()
+    ws_res = binding.reserve_workspace(t_rc, N, MAXB)                 # the free list is built once and then kept up
     total_pruned = 0
     for step in range(steps):
         kn = wl.normal_bf16(wl.rng_for(1000 + step, 0), (N, Hkv, D)); vn = wl.normal_bf16(wl.rng_for(1000 + step, 1), (N, Hkv, D))
@@ -163,7 +210,7 @@ def _decode_loop(NP):
             break
         bidx = live[wl.rng_for(1000 + step, 4).random(live.size) < 0.3].astype(np.int32)
         # device
-        pruned, n_pruned, new_pages = binding.reserve_pages(t_scores, t_rc, t_bt, t_sl, status=st)
+        pruned, n_pruned, new_pages = binding.reserve_pages(t_scores, t_rc, t_bt, t_sl, workspace=ws_res, status=st)
         binding.append_kv(dev_bits(kn), dev_bits(vn), t_k, t_v, t_bt, t_sl, refcounts=t_rc, status=st)
         out = binding.paged_decode_attn(dev_bits(q), t_k, t_v, t_bt, t_sl, status=st)
         logits, probs = binding.step_score(dev_bits(hidden), dev(bidx), t_W1, t_b1, t_W2, t_b2, trace_of=dev(bidx),

@@ -65,6 +65,7 @@ def test_decode_step_replayed_as_hip_graph_matches_eager():
         return [t.clone() for t in (out, logits, probs, pruned[: int(n_pruned.item())], new_pages, n_pruned,
                                     S["rc"], S["bt"], S["sl"], S["scores"], S["sum"], S["cnt"])]
 
+    binding.freelist_rebuild(S["rc"], ws_res)                         # the free list lives in ws_res from here on
     eager = []
     for step in range(steps):
         feed(step)
@@ -75,6 +76,7 @@ def test_decode_step_replayed_as_hip_graph_matches_eager():
 
     for name, t in init.items():
         S[name].copy_(t)
+    binding.freelist_rebuild(S["rc"], ws_res)
     feed(0)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -82,6 +84,7 @@ def test_decode_step_replayed_as_hip_graph_matches_eager():
         one_step()
     for name, t in init.items():                                      # capture launches nothing, but be explicit
         S[name].copy_(t)
+    binding.freelist_rebuild(S["rc"], ws_res)                         # the reference counts were reset: so is the list
     for step in range(steps):
         feed(step)
         graph.replay()

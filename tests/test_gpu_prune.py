@@ -121,6 +121,51 @@ def test_device_reported_errors_leave_selection_state_untouched():
     assert got[2][lay.block_tables[t, 3]] == 0                                                  # not driven negative
 
 
+@pytest.mark.parametrize("big", [False, True])
+def test_documented_post_state_after_a_bad_page_id_or_reference_count(big):
+    """An error met while releasing (a page id outside the pool, a reference count that is already 0) is
+    reported and that one entry skipped; everything else of the call is carried out.  The oracle, by its own
+    convention, changes nothing on any error: the two are compared on what both define -- which traces are
+    pruned -- and the GPU's post-state is checked against the rule the header documents.  Both kernel paths:
+    the one-workgroup path (small) and the three-kernel path (k * row width above its limit)."""
+    N, k = (40, 24) if big else (10, 3)
+    lay = _layout(48 if big else 47, N, 32, 6000 if big else 100, 8000 if big else 300)
+    assert (k * lay.MAXB > 8192) == big
+    scores = wl.rng_for(47, 2).uniform(0, 1, N).astype(np.float32)
+    order = np.argsort(scores, kind="stable")[:k]
+    t_bad_page, t_bad_rc = int(order[0]), int(order[1])
+    bt = lay.block_tables.copy(); rc = lay.refcounts.copy()
+    lost = int(bt[t_bad_page, 3])                                  # a private page whose entry is overwritten
+    bt[t_bad_page, 3] = lay.NP + 11
+    zero_page = int(bt[t_bad_rc, 4])
+    rc[zero_page] = 0
+    st = new_status()
+    t_rc, t_bt, t_sl = dev(rc), dev(bt), dev(lay.seq_lens.copy())
+    pruned, freed, nf = binding.prune_free(dev(scores), k, t_rc, t_bt, t_sl, status=st)
+    torch.cuda.synchronize()
+    assert binding.ERROR_NAMES[int(st.item())] in ("STEP_EPAGE", "STEP_EREFCOUNT")
+    g_rc, g_bt, g_sl = t_rc.cpu().numpy(), t_bt.cpu().numpy(), t_sl.cpu().numpy()
+    g_pruned = pruned.cpu().numpy()[:k]; g_freed = freed.cpu().numpy()[: int(nf.item())]
+    assert g_pruned.tolist() == order.tolist()                        # the selection is unaffected
+    surv = np.setdiff1d(np.arange(N), order)
+    assert np.array_equal(g_bt[surv], bt[surv]) and np.array_equal(g_sl[surv], lay.seq_lens[surv])   # survivors untouched
+    assert np.all(g_bt[order] == -1) and np.all(g_sl[order] == 0)     # pruned rows cleared all the same
+    want = rc.copy()
+    for t in order:
+        for j in range((lay.seq_lens[t] + P - 1) // P):
+            pg = bt[t, j]
+            if 0 <= pg < lay.NP and want[pg] > 0:
+                want[pg] -= 1
+    assert np.array_equal(g_rc, want) and g_rc.min() >= 0             # every valid entry released once, none negative
+    assert g_rc[lost] == 1 and g_rc[zero_page] == 0                   # the page behind the bad entry stays referenced
+    assert np.all(np.diff(g_freed) > 0)                               # still ascending, and exactly the pages that reached 0
+    assert np.array_equal(g_freed, np.nonzero((want == 0) & (rc > 0))[0])
+    with pytest.raises(oracle.OracleError):
+        o_rc, o_bt, o_sl = rc.copy(), bt.copy(), lay.seq_lens.copy()
+        oracle.prune_free(scores, k, o_rc, o_bt, o_sl, P)
+    assert np.array_equal(o_rc, rc) and np.array_equal(o_bt, bt)      # the oracle's convention: nothing modified
+
+
 def test_host_reported_errors():
     lay = _layout(43, 4, 0, 20, 60)
     scores = dev(np.zeros(4, np.float32))
