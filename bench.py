@@ -53,6 +53,10 @@ def parse_args():
     ap.add_argument("--graph", action="store_true", help="record the K timed steps as one HIP graph and time its replay")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="only run libstep's plain copy kernel on MIB MiB (profiler byte-counter calibration)")
+    ap.add_argument("--launch-floor", action="store_true",
+                    help="also time a 16-byte copy kernel launched right after every attention call of the profiled "
+                         "steps: the duration of a kernel that does nothing, in the state the step's small kernels "
+                         "start in (reported as launch_floor_us)")
     ap.add_argument("--read-probe", action="store_true",
                     help="only run the bare tile-read probe on the config's pool and private pages (what HBM delivers "
                          "to the streaming kernel's access pattern with no arithmetic behind it)")
@@ -204,9 +208,15 @@ def main():
         binding.ScoreDims(sc.hidden.shape[0], sc.hidden.shape[1], sc.W1.shape[0], B, s.N, sc.act)), dev)
     ws_prune = binding.new_workspace(binding.prune_workspace_bytes(s.N, lay.MAXB, lay.NP), dev)
 
+    floor_src = torch.zeros(16, dtype=torch.uint8, device=dev)
+    floor_dst = torch.zeros(16, dtype=torch.uint8, device=dev)
+    floor_on = [False]
+
     def step(i):
         if layers == 1:
             binding.paged_decode_attn(q, k_pages, v_pages, bt_s[i], sl_s[i], out=out, workspace=ws_attn, status=status)
+            if floor_on[0]:
+                binding.calib_copy(floor_dst, floor_src)
         else:  # the per-block shared-prefix lengths are found once per step and shared by every layer's attention
             binding.attn_plan(q, k_pages, bt_s[i], sl_s[i], ws_attn, status=status)
             for l in range(layers):
@@ -271,6 +281,7 @@ def main():
     # the same K steps again with HIP events attached to every kernel launch (the event records cost a few
     # microseconds each, so they stay out of the step time above)
     cap = K * (3 * layers + 12)
+    floor_on[0] = args.launch_floor
     binding.profile_begin(cap)
     for i in range(W + K, W + 2 * K):
         step(i)
@@ -284,7 +295,9 @@ def main():
     stage1_ms = per_kernel["attn_partial"]
     assert len(stage1_ms) == K * layers
     breakdown = {name: round(1e3 * float(np.sum(v)) / K, 2) for name, v in per_kernel.items()}   # us per step
-    launches_per_step = len(timed) / K
+    floor_ms = per_kernel.pop("calib_copy", None)
+    breakdown.pop("calib_copy", None)
+    launches_per_step = (len(timed) - (len(floor_ms) if floor_ms else 0)) / K
 
     ms_per_step = (t1 - t0) * 1e3 / K
     value = s.N / (ms_per_step * 1e-3)                              # trace-tokens per second
@@ -349,6 +362,9 @@ def main():
         "roofline": roofline, "attention": attention, "step_breakdown": breakdown,
     }
 
+    if floor_ms:
+        result["launch_floor_us"] = {"avg": round(1e3 * float(np.mean(floor_ms)), 2), "min": round(1e3 * float(np.min(floor_ms)), 2),
+                                     "what": "a 16-byte copy kernel (one workgroup) right after each attention call"}
     if args.mode == "loop":
         # nothing else ends a trace in this loop, so the difference is what the memory trigger pruned
         result["config"]["traces_pruned_by_memory_trigger"] = live_at_start - int((sl_l > 0).sum().item())

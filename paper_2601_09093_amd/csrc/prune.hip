@@ -9,8 +9,8 @@
 //                validates lengths and scores and clears the freed-page bitmap.
 // prune_release: one thread per (pruned trace, block-table entry): atomic decrement of the page's
 //                refcount; the decrement that reaches zero sets the page's bit in the bitmap.
-// prune_compact: one workgroup scans the bitmap in ascending page order (popcount + prefix sum)
-//                and writes the freed page ids; then marks the pruned traces dead.
+// prune_compact: the bitmap in ascending page order (popcount + prefix sum) gives the freed page ids, 1024
+//                bitmap words per workgroup; then the pruned traces are marked dead.
 // prune_fused  : all of the above in one workgroup, for small problems.
 #include <mutex>
 
@@ -151,29 +151,34 @@ __global__ __launch_bounds__(256) void prune_release(const PruneArgs a)
     *entry = -1;
 }
 
+// One workgroup per 1024 bitmap words, one word per thread.  A workgroup needs the number of freed pages
+// in the words before its own: it counts them itself (the whole bitmap is a few kilobytes, read from the
+// caches), so the workgroups need nothing from each other; the last one also reports the total.
 __global__ __launch_bounds__(kSelThreads) void prune_compact(const PruneArgs a)
 {
     __shared__ int scratch[32];
     const int tid = threadIdx.x;
     const int k_eff = a.hdr->k_eff;
-    const int per = (a.words + kSelThreads - 1) / kSelThreads;
-    const int w0 = min(tid * per, a.words), w1 = min(w0 + per, a.words);
-    int cnt = 0;
-    if (k_eff > 0)
-        for (int wv = w0; wv < w1; ++wv) cnt += __popc(a.bitmap[wv]);
+    const int seg0 = blockIdx.x * kSelThreads;
+    const int wv = seg0 + tid;
+    u32 bits = 0;
+    int before = 0;
+    if (k_eff > 0) {
+        if (wv < a.words) bits = a.bitmap[wv];
+        for (int w = tid; w < seg0; w += kSelThreads) before += __popc(a.bitmap[w]);
+    }
+    int base = 0;
+    if (blockIdx.x > 0) (void)block_excl_scan(before, scratch, &base);  // uniform branch; base = sum over the workgroup
     int total;
-    int pos = block_excl_scan(cnt, scratch, &total);
-    if (k_eff > 0 && cnt > 0)
-        for (int wv = w0; wv < w1; ++wv) {
-            u32 bits = a.bitmap[wv];
-            while (bits) {
-                const int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                a.freed_pages[pos++] = wv * 32 + b;
-            }
-        }
-    if (tid == 0) *a.n_freed = total;
-    for (int r = tid; r < k_eff; r += kSelThreads) a.seq_lens[a.pruned[r]] = 0;
+    int pos = base + block_excl_scan(__popc(bits), scratch, &total);
+    while (bits) {
+        const int b = __ffs(bits) - 1;
+        bits &= bits - 1;
+        a.freed_pages[pos++] = wv * 32 + b;
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) *a.n_freed = base + total;
+    if (blockIdx.x == 0)
+        for (int r = tid; r < k_eff; r += kSelThreads) a.seq_lens[a.pruned[r]] = 0;
 }
 
 // Small problems (N <= 1024 traces, at most 8192 block-table entries to release, a bitmap that fits
@@ -202,10 +207,10 @@ __global__ __launch_bounds__(kSelThreads) void prune_fused(const PruneArgs a)
         int L = 0;
         if (tid < a.N) {
             L = a.seq_lens[tid];
+            const float s = a.scores[tid];  // requested together with the length (a dead trace's score is not looked at)
             if (L < 0 || (long long)L > (long long)a.MAXB * a.P) {
                 atomicCAS(&err, 0, (int)STEP_ELEN);
             } else if (L > 0) {
-                const float s = a.scores[tid];
                 if (s != s) atomicCAS(&err, 0, (int)STEP_ENAN);
                 key = ((u64)order_key(s) << 32) | (u32)tid;
             }
@@ -253,28 +258,53 @@ __global__ __launch_bounds__(kSelThreads) void prune_fused(const PruneArgs a)
         __syncthreads();
     }
     if (tid < a.k) a.pruned[tid] = (int32_t)(u32)keys[tid];
-    // release: one (pruned trace, block-table entry) per thread and trip
+    // release: (pruned trace, block-table entry) pairs, four per thread and trip: first the four entries are
+    // requested, then the four decrements, then their results are looked at -- two memory round trips per trip
+    // instead of two per entry
     const int entries = a.k * a.MAXB;
-    for (int e = tid; e < entries; e += kSelThreads) {
-        const int r = e / a.MAXB, j = e - r * a.MAXB;
-        const int t = (int)(u32)keys[r];
-        const int nb = (lens[t] + a.P - 1) / a.P;
-        int32_t *entry = a.block_tables + (size_t)t * a.MAXB + j;
-        if (j < nb) {
-            const int p = *entry;
-            if ((u32)p >= (u32)a.NP) {
-                report(a.status, STEP_EPAGE);
-            } else {
-                const int old = atomicSub(&a.refcounts[p], 1);
-                if (old <= 0) {
-                    atomicAdd(&a.refcounts[p], 1);
-                    report(a.status, STEP_EREFCOUNT);
-                } else if (old == 1) {
-                    atomicOr(&bitmap[p >> 5], 1u << (p & 31));
+    constexpr int kRel = 4;
+    for (int e0 = tid; e0 < entries; e0 += kRel * kSelThreads) {
+        int32_t *entry[kRel];
+        int page[kRel], old[kRel];
+        bool used[kRel];
+#pragma unroll
+        for (int u = 0; u < kRel; ++u) {
+            const int e = e0 + u * kSelThreads;
+            used[u] = false;
+            entry[u] = nullptr;
+            page[u] = -1;
+            if (e < entries) {
+                const int r = e / a.MAXB, j = e - r * a.MAXB;
+                const int t = (int)(u32)keys[r];
+                entry[u] = a.block_tables + (size_t)t * a.MAXB + j;
+                used[u] = j < (lens[t] + a.P - 1) / a.P;
+                if (used[u]) page[u] = *entry[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kRel; ++u) {
+            old[u] = 1 << 30;
+            if (used[u]) {
+                if ((u32)page[u] >= (u32)a.NP) {
+                    report(a.status, STEP_EPAGE);
+                    used[u] = false;
+                } else {
+                    old[u] = atomicSub(&a.refcounts[page[u]], 1);
                 }
             }
         }
-        *entry = -1;
+#pragma unroll
+        for (int u = 0; u < kRel; ++u) {
+            if (used[u]) {
+                if (old[u] <= 0) {
+                    atomicAdd(&a.refcounts[page[u]], 1);
+                    report(a.status, STEP_EREFCOUNT);
+                } else if (old[u] == 1) {
+                    atomicOr(&bitmap[page[u] >> 5], 1u << (page[u] & 31));
+                }
+            }
+            if (entry[u]) *entry[u] = -1;
+        }
     }
     __syncthreads();
     // compact the bitmap in ascending page order
@@ -336,7 +366,7 @@ int run_prune(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *score
     launch_kernel(kKernPruneSelect, prune_select, dim3(1), dim3(kSelThreads), s, a);
     if (k > 0 && MAXB > 0)
         launch_kernel(kKernPruneRelease, prune_release, dim3((MAXB + 255) / 256, k), dim3(256), s, a);
-    launch_kernel(kKernPruneCompact, prune_compact, dim3(1), dim3(kSelThreads), s, a);
+    launch_kernel(kKernPruneCompact, prune_compact, dim3((unsigned)((a.words + kSelThreads - 1) / kSelThreads > 0 ? (a.words + kSelThreads - 1) / kSelThreads : 1)), dim3(kSelThreads), s, a);
     return launch_status();
 }
 

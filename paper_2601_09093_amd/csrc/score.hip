@@ -93,33 +93,76 @@ __device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, fl
     const float b2 = a.b2[0];
     const bool state = a.score_sum != nullptr;
     const bool staged = state && a.N <= kStateMax;  // keep the sequential replay off global memory
-    if (staged)
-        for (int t = tid; t < a.N; t += kThreads) {
-            sum_s[t] = a.score_sum[t];
-            cnt_s[t] = a.score_cnt[t];
+    // the state is requested first and parked in LDS only after the partial logits of the first boundaries have
+    // been requested and summed, so the cold loads overlap
+    constexpr int kPer = kStateMax / kThreads;
+    float rs[kPer];
+    int rc[kPer];
+    if (staged) {
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads;
+            rs[u] = t < a.N ? a.score_sum[t] : 0.f;
+            rc[u] = t < a.N ? a.score_cnt[t] : 0;
         }
+    }
+    bool parked = false;
+    auto park_state = [&]() {
+        if (staged && !parked) {
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int t = tid + u * kThreads;
+                if (t < a.N) {
+                    sum_s[t] = rs[u];
+                    cnt_s[t] = rc[u];
+                }
+            }
+        }
+        parked = true;
+    };
+    const int lane = tid & 63, wv = tid >> 6;
     for (int base = 0; base < a.B; base += kFinishChunk) {
         const int nbd = min(kFinishChunk, a.B - base);
-        for (int bb = tid; bb < nbd; bb += kThreads) {
-            const int b = base + bb;
-            // partial logits are summed in a fixed order, four independent accumulators in flight
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-            int t = 0;
-            for (; t + 3 < mt; t += 4) {
-                s0 += ld_dev(&a.plogit[(size_t)(t + 0) * a.B + b]);
-                s1 += ld_dev(&a.plogit[(size_t)(t + 1) * a.B + b]);
-                s2 += ld_dev(&a.plogit[(size_t)(t + 2) * a.B + b]);
-                s3 += ld_dev(&a.plogit[(size_t)(t + 3) * a.B + b]);
+        // logit of a boundary = b2 + sum over the row tiles of its partial logits, in a fixed order: lane l adds the
+        // tiles l, l + 64, ... in ascending order, then the lanes are added pairwise (xor 32, 16, ... 1).  A wave takes
+        // four boundaries at a time so that their loads are in flight together.
+        constexpr int kB4 = 4;
+        for (int bb0 = wv * kB4; bb0 < nbd; bb0 += kWaves * kB4) {
+            float acc[kB4];
+#pragma unroll
+            for (int u = 0; u < kB4; ++u) acc[u] = 0.f;
+            for (int t0 = 0; t0 < mt; t0 += 64 * 4) {
+                float v[4][kB4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int u = 0; u < kB4; ++u) {
+                        const int t = t0 + r * 64 + lane, bb = bb0 + u;
+                        v[r][u] = (t < mt && bb < nbd) ? ld_dev(&a.plogit[(size_t)t * a.B + base + bb]) : 0.f;
+                    }
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int u = 0; u < kB4; ++u) acc[u] += v[r][u];
             }
-            for (; t < mt; ++t) s0 += ld_dev(&a.plogit[(size_t)t * a.B + b]);
-            const float logit = b2 + ((s0 + s1) + (s2 + s3));
-            const float prob = 1.0f / (1.0f + expf(-logit));
-            a.logits[b] = logit;
-            a.probs[b] = prob;
-            prob_s[bb] = prob;
-            trace_s[bb] = state ? a.trace_of[b] : 0;
+#pragma unroll
+            for (int u = 0; u < kB4; ++u) {
+                float x = acc[u];
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+                const int bb = bb0 + u;
+                if (lane == 0 && bb < nbd) {
+                    const float logit = b2 + x;
+                    const float prob = 1.0f / (1.0f + expf(-logit));
+                    a.logits[base + bb] = logit;
+                    a.probs[base + bb] = prob;
+                    prob_s[bb] = prob;
+                }
+            }
         }
+        for (int bb = tid; bb < nbd; bb += kThreads) trace_s[bb] = state ? a.trace_of[base + bb] : 0;
         if (!state) continue;  // uniform
+        park_state();
         __syncthreads();
         if (tid == 0) {
             // boundaries in index order: fp32 addition is not associative and a trace may own several
@@ -141,6 +184,7 @@ __device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, fl
         __syncthreads();
     }
     if (!state) return;
+    park_state();  // (no boundaries: nothing above has done it)
     __threadfence_block();
     __syncthreads();
     for (int t = tid; t < a.N; t += kThreads) {
@@ -177,6 +221,23 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
     const int m0 = mt * 16;
     const int b0 = bz * (16 * kBT);
 
+    // Requested before anything they do not depend on: this wave's first 64 bytes of W1 per lane, and the bias and
+    // output weights of the workgroup's 16 hidden units (used only after the sums are complete).
+    const uint16_t *wrow = a.W1 + (size_t)(m0 + row16) * a.d;
+    const int it0 = chunk * a.chunk_iters, it1 = min(it0 + a.chunk_iters, a.d / 128);
+    uint4 av[4];
+    if (it0 + w < it1) {
+        const uint4 *wp = reinterpret_cast<const uint4 *>(wrow + (it0 + w) * 128 + kg * 32);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) av[s] = wp[s];
+    }
+    float b1v[4], w2v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        b1v[i] = a.b1[m0 + kg * 4 + i];
+        w2v[i] = bf16_lo((u32)a.W2[m0 + kg * 4 + i]);
+    }
+
     // rows of `hidden` feeding the B operand of each boundary tile (column = lane % 16)
     const uint16_t *xrow[kBT];
 #pragma unroll
@@ -193,21 +254,21 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
         xrow[t] = a.hidden + (size_t)rix * a.d;
     }
     const bool tile1 = (b0 + 16 < a.B);  // wave-uniform: second boundary tile in use
-    const uint16_t *wrow = a.W1 + (size_t)(m0 + row16) * a.d;
 
     f32x4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
-    const int it0 = chunk * a.chunk_iters, it1 = min(it0 + a.chunk_iters, a.d / 128);
     for (int it = it0 + w; it < it1; it += kWaves) {
         // the contraction index is permuted identically for both operands: lane group kg takes the
         // 32 consecutive values kbase + 32 kg .. +32, eight per MFMA, so a lane reads 64 contiguous
         // bytes per iteration and the four groups cover 256 contiguous bytes of the row
         const int kbase = it * 128 + kg * 32;
-        const uint4 *wp = reinterpret_cast<const uint4 *>(wrow + kbase);
         const uint4 *x0 = reinterpret_cast<const uint4 *>(xrow[0] + kbase);
         const uint4 *x1 = reinterpret_cast<const uint4 *>(xrow[1] + kbase);
-        uint4 av[4], bv0[4], bv1[4];
+        uint4 bv0[4], bv1[4];
+        if (it != it0 + w) {  // (the first iteration's W1 is already on its way)
+            const uint4 *wp = reinterpret_cast<const uint4 *>(wrow + kbase);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) av[s] = wp[s];
+            for (int s = 0; s < 4; ++s) av[s] = wp[s];
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) bv0[s] = x0[s];
         if (tile1) {
@@ -254,10 +315,21 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
         if (w < kBT && b < a.B) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) z[i] = 0.f;
-            for (int ch = 0; ch < a.nchunk; ++ch) {
-                const float *src = a.partial + (((size_t)ch * MT + mt) * a.B + b) * 16 + kg * 4;
+            for (int ch0 = 0; ch0 < a.nchunk; ch0 += 8) {  // eight chunks requested together, added in chunk order
+                float v[8][4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) z[i] += ld_dev(src + i);
+                for (int u = 0; u < 8; ++u) {
+                    const int ch = min(ch0 + u, a.nchunk - 1);
+                    const float *src = a.partial + (((size_t)ch * MT + mt) * a.B + b) * 16 + kg * 4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[u][i] = ld_dev(src + i);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (ch0 + u < a.nchunk) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) z[i] += v[u][i];
+                    }
             }
         }
     }
@@ -265,10 +337,7 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
     if (w < kBT) {
         float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = m0 + kg * 4 + i;
-            s = fmaf(bf16_lo((u32)a.W2[row]), activate(z[i] + a.b1[row], a.act), s);
-        }
+        for (int i = 0; i < 4; ++i) s = fmaf(w2v[i], activate(z[i] + b1v[i], a.act), s);
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
         if (kg == 0 && b < a.B) st_dev(&a.plogit[(size_t)mt * a.B + b], s);
