@@ -42,7 +42,7 @@ enum step_error {
     STEP_ENAN = 19,      /* device: NaN score on a live trace                                    */
     STEP_EREFCOUNT = 20, /* device: a released page had refcount <= 0                            */
     STEP_EKLIVE = 21,    /* device: k larger than the number of live traces                      */
-    STEP_EPLAN = 22,     /* device: the workspace holds no plan made for these dims              */
+    STEP_EPLAN = 22,     /* device: the workspace holds no shared-prefix lengths made for these dims */
     STEP_EFREELIST = 23  /* device: no free list in the workspace, or it disagrees with refcounts */
 };
 
@@ -93,24 +93,25 @@ int32_t step_attn_waves_per_head(const step_attn_dims *dims);
  * softmax weights are rounded to bf16 before they multiply V (the normaliser is summed from the
  * same rounded weights).  Result within 2e-2
  * max-abs of the float64 definition for N(0,1) inputs.
- * Leading pages that every live trace has in its block-table row (a shared prompt, up to 1024 whole
- * pages) are found on the device and computed once for all traces on the matrix cores; the
- * environment variable STEP_ATTN_PREFIX=0, read once, turns that off (testing aid: they are then
- * streamed per trace like private pages).  A workspace that holds no plan for these dims makes
- * paged_decode_attn_planned report STEP_EPLAN.
+ * Shared prompts: the traces are taken in blocks of 16 * QT / G consecutive indices (QT = 2 once N * G >= 256,
+ * else 1); the leading block-table entries that every live trace of a block has in common (whole pages all
+ * of them attend to completely, up to 1024) are found on the device and computed once per block on the
+ * matrix cores.  The environment variable STEP_ATTN_PREFIX=0, read once, turns that off (testing aid: the
+ * pages are then streamed per trace like private pages).  N * MAXB must stay below 2^30.
  */
 int paged_decode_attn(const step_attn_dims *dims, const uint16_t *q, const uint16_t *k_pages,
                       const uint16_t *v_pages, const int32_t *block_tables, const int32_t *seq_lens,
                       uint16_t *out, void *workspace, size_t workspace_bytes, int32_t *status, void *stream);
 
 /*
- * The same call in two halves, for a model with several layers: all layers of one decode step see
- * the same block_tables and seq_lens, so the split of the work is planned once per step and every
- * layer's attention reuses it.  step_attn_plan writes the plan into `workspace`;
- * paged_decode_attn_planned is paged_decode_attn without the planning kernel and must be given the
- * same dims, block_tables, seq_lens and workspace, unchanged since the plan was made (the layers run
- * one after another on one stream and share the workspace).  Same arguments, layouts and errors as
- * paged_decode_attn.
+ * The same call in two halves, for a model with several layers: all layers of one decode step see the
+ * same block_tables and seq_lens, so the per-block shared-prefix lengths are found once per step and every
+ * layer's attention reuses them.  step_attn_plan finds them (and reports lengths outside the block-table
+ * row) and leaves them, with a stamp of the dims, in `workspace`; paged_decode_attn_planned is
+ * paged_decode_attn without that search and must be given the same dims, block_tables, seq_lens and
+ * workspace, unchanged since (the layers run one after another on one stream and share the workspace).
+ * On a workspace whose stamp is not the one of its dims it reports STEP_EPLAN (the output is then
+ * unspecified; no access leaves the arrays).  Same arguments, layouts and errors as paged_decode_attn.
  */
 int step_attn_plan(const step_attn_dims *dims, const int32_t *block_tables, const int32_t *seq_lens,
                    void *workspace, size_t workspace_bytes, int32_t *status, void *stream);

@@ -163,7 +163,7 @@ def paged_decode_attn(q, k_pages, v_pages, block_tables, seq_lens, out=None, sca
 
 
 def attn_plan(q, k_pages, block_tables, seq_lens, workspace, scale=None, status=None):
-    """Plan one decode step's attention work into `workspace` (shared by all layers of the step)."""
+    """Find the per-block shared-prefix lengths of one decode step into `workspace` (shared by all layers of the step)."""
     dims = attn_dims(q, k_pages, block_tables, scale)
     rc = lib().step_attn_plan(ctypes.byref(dims), _dev(block_tables, (torch.int32,), "block_tables"),
                               _dev(seq_lens, (torch.int32,), "seq_lens"), _dev(workspace, (torch.uint8,), "workspace"),
@@ -174,7 +174,7 @@ def attn_plan(q, k_pages, block_tables, seq_lens, workspace, scale=None, status=
 
 
 def paged_decode_attn_planned(q, k_pages, v_pages, block_tables, seq_lens, out, workspace, scale=None, status=None):
-    """paged_decode_attn without the planning kernel; `workspace` holds the plan made by attn_plan."""
+    """paged_decode_attn without the shared-prefix search; `workspace` holds what attn_plan found."""
     dims = attn_dims(q, k_pages, block_tables, scale)
     rc = lib().paged_decode_attn_planned(
         ctypes.byref(dims), _dev(q, _BF16_OK, "q"), _dev(k_pages, _BF16_OK, "k_pages"),

@@ -72,7 +72,7 @@ int waves_per_head(const step_attn_dims *d)
     return wh;
 }
 
-// The shared prefix goes to the matrix cores (attn_prefix) unless the environment variable
+// Shared prefixes go to the matrix cores (attn_front) unless the environment variable
 // STEP_ATTN_PREFIX is "0" (read once; testing aid: stage 1 then streams the prefix per trace).
 bool prefix_enabled()
 {

@@ -28,7 +28,6 @@ constexpr int kMaxParts = 8;      // a shared prefix is cut into at most this ma
 constexpr int kMaxPlanN = 2048;   // traces per call
 constexpr int kMaxWh = 2048;      // streaming waves per KV head
 constexpr int kMaxShared = 1024;  // pages of common prefix looked for per block (16384 tokens)
-constexpr int kMaxTB = 32;        // traces per block at most (G = 1, two query tiles)
 
 struct PlanHeader {   // 256 bytes at the start of the workspace
     int32_t stamp;    // hash of the dims the per-block prefix lengths were found for (AttnArgs::stamp), never 0

@@ -8,7 +8,7 @@ namespace attn {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// The matrix-core form of one page pair, shared by attn_prefix and attn_partial_mfma.
+// The matrix-core form of one page pair, shared by attn_front and attn_partial_mfma.
 // Operand layouts (lane = 16 * gr + c; a lane holds 8 contraction slots, and slot e of lane group gr
 // of A meets slot e of lane group gr of B):
 //   logits  S^T = K Q^T   A = K tile: row = token c, slots = d in [32 kb + 8 gr, +8)   (16-byte load)

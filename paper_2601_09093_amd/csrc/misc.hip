@@ -78,7 +78,7 @@ extern "C" const char *step_strerror(int code)
         case STEP_ENAN: return "STEP_ENAN: NaN score on a live trace";
         case STEP_EREFCOUNT: return "STEP_EREFCOUNT: released page had refcount <= 0";
         case STEP_EKLIVE: return "STEP_EKLIVE: k exceeds the number of live traces";
-        case STEP_EPLAN: return "STEP_EPLAN: the workspace holds no attention plan made for these dims";
+        case STEP_EPLAN: return "STEP_EPLAN: the workspace holds no shared-prefix lengths made for these dims (step_attn_plan)";
         case STEP_EFREELIST: return "STEP_EFREELIST: the workspace holds no free list for this pool, or it does not match the refcounts";
     }
     return "unknown libstep error";

@@ -195,7 +195,7 @@ def test_host_reported_errors():
     with pytest.raises(binding.StepError) as e:
         binding.paged_decode_attn(bad, kb, kb, tb, tl, workspace=torch.zeros(1 << 20, dtype=torch.uint8, device=DEV))
     assert e.value.code == 1
-    for shape_q, shape_k in (((2049, 4, 64), (2, 1, 16, 64)),      # more traces than the planner handles
+    for shape_q, shape_k in (((2049, 4, 64), (2, 1, 16, 64)),      # more traces than a call takes
                              ((1, 6, 64), (2, 2, 16, 64)),         # group size 3
                              ((1, 5, 64), (2, 2, 16, 64))):        # Hq not a multiple of Hkv
         bq = torch.zeros(shape_q, dtype=torch.int16, device=DEV)
@@ -210,18 +210,11 @@ def test_host_reported_errors():
     torch.cuda.synchronize()
 
 
-def _shared_layout(seed, lens, shared_pages, P=16, extra_pool=7):
-    """Traces whose first `shared_pages` block-table entries are identical (caller keeps lens >= them)."""
-    lens = np.asarray(lens)
-    lay = wl.build_layout(lens, shared_pages * P, P, wl.rng_for(seed, 0), slack=1.1)
-    return lay
-
-
 @pytest.mark.parametrize("case", ["many_short", "more_traces_than_waves", "single_trace", "all_shared",
                                   "long_prefix", "prefix_beyond_search_cap", "prefix_ends_ragged",
-                                  "most_traces_the_planner_takes", "two_traces"])
-def test_planner_corner_cases(case):
-    """Shapes that push the work planner: shared-prefix detection, sub-chunking, runs that span many
+                                  "most_traces_a_call_takes", "two_traces"])
+def test_corner_cases_of_the_cut(case):
+    """Shapes that push the way a call is cut: shared-prefix detection, sub-chunking, runs that span many
     traces, more live traces than waves per KV head, traces that lie entirely inside the prefix."""
     r = wl.rng_for(900, 0)
     D, Hq, Hkv = 128, 8, 2
@@ -246,7 +239,7 @@ def test_planner_corner_cases(case):
         lens = np.array([64 + 9, 64 + 9, 64 + 700])
         lay = wl.build_layout(lens, 64, P, wl.rng_for(906, 0))
         lay.block_tables[1, 4] = lay.block_tables[0, 4]      # traces 0 and 1 also share their ragged last page
-    elif case == "most_traces_the_planner_takes":
+    elif case == "most_traces_a_call_takes":
         lens = 64 + r.integers(1, 120, 2048); lens[5::97] = 0   # N = 2048, four shared pages
         lay = wl.build_layout(lens, 64, P, wl.rng_for(910, 0), slack=1.0)
         Hq, Hkv = 4, 1                                           # one KV head: 1024 waves on it
@@ -335,7 +328,7 @@ def test_random_shapes_and_length_mixes(seed):
 @pytest.mark.parametrize("seed", range(24))
 def test_random_trace_counts_and_prefix_lengths(seed):
     """A second seeded sweep, wider in the number of traces (1 to 600) and in the shared prefix (0 to 300
-    pages, around the 256-column blocks of the planner's search), with traces that end exactly at the
+    pages, around the 128-column trips of the shared-prefix search), with traces that end exactly at the
     prefix, many dead traces and short tails."""
     r = wl.rng_for(90000 + seed, 0)
     D = int(r.choice([64, 128, 128]))

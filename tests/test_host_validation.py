@@ -38,7 +38,7 @@ def test_attention_rejects_bad_dims_and_pointers(L):
                 binding.AttnDims(64, 32, 8, 128, 32, 2112, 100000, 0.1),     # page size
                 binding.AttnDims(64, 30, 8, 128, 16, 2112, 100000, 0.1),     # Hq % Hkv
                 binding.AttnDims(64, 24, 8, 128, 16, 2112, 100000, 0.1),     # group size 3
-                binding.AttnDims(4096, 32, 8, 128, 16, 2112, 100000, 0.1),   # more traces than the planner takes
+                binding.AttnDims(4096, 32, 8, 128, 16, 2112, 100000, 0.1),   # more traces than a call takes
                 binding.AttnDims(-1, 32, 8, 128, 16, 2112, 100000, 0.1),
                 binding.AttnDims(64, 32, 8, 128, 16, -5, 100000, 0.1)):
         assert binding.attn_workspace_bytes(bad) == 0 and binding.attn_waves_per_head(bad) == 0
@@ -124,3 +124,38 @@ def test_prune_and_engine_calls_reject_bad_arguments(L):
     assert L.step_weighted_vote(-1, vp(A), vp(A), vp(A), vp(A), None, None) == EINVAL
     assert L.step_weighted_vote(8, vp(0), vp(A), vp(A), vp(A), None, None) == EINVAL
     assert L.step_weighted_vote(8, vp(A), vp(A), vp(0), vp(A), None, None) == EINVAL
+
+
+def test_free_list_static_prune_and_measurement_aids_reject_bad_arguments(L):
+    rneed = int(L.step_reserve_workspace_bytes(0, 0, 5000))
+    assert rneed >= 256 + 5000 // 8
+    assert L.step_freelist_rebuild(-1, vp(A), vp(A), rneed, None) == EINVAL
+    assert L.step_freelist_rebuild(5000, vp(0), vp(A), rneed, None) == EINVAL
+    assert L.step_freelist_rebuild(5000, vp(A), vp(0), rneed, None) == EWORKSPACE
+    assert L.step_freelist_rebuild(5000, vp(A), vp(A + 64), rneed, None) == EWORKSPACE
+    assert L.step_freelist_rebuild(5000, vp(A), vp(A), rneed - 1, None) == EWORKSPACE
+    assert L.step_freelist_add(5000, vp(A), vp(0), 10, vp(A), rneed, None, None) == EINVAL      # n_freed is required
+    assert L.step_freelist_add(5000, vp(0), vp(A), 10, vp(A), rneed, None, None) == EINVAL
+    assert L.step_freelist_add(5000, vp(A), vp(A), -1, vp(A), rneed, None, None) == EINVAL
+    assert L.step_freelist_add(5000, vp(A), vp(A), 10, vp(A), rneed - 1, None, None) == EWORKSPACE
+
+    def static(N=64, MAXB=100, NP=5000, P=16, scores=A, k=1, rc=A, bt=A, sl=A, pruned=A, freed=A, nf=A):
+        return L.prune_free_static(N, MAXB, NP, P, vp(scores), k, vp(rc), vp(bt), vp(sl), vp(pruned), vp(freed), vp(nf),
+                                   None, None)
+    assert static(N=-1) == EINVAL and static(k=65) == EINVAL and static(nf=0) == EINVAL and static(rc=0) == EINVAL
+    assert static(P=0) == EINVAL and static(pruned=0) == EINVAL
+    assert static(NP=L.step_prune_static_max_pages() + 1) == EWORKSPACE        # larger than the static bitmap covers
+
+    probe = L.step_read_probe
+    assert probe(vp(0), vp(A), vp(A), 128, 10, 8, 1000, 0, 1, vp(A), None) == EINVAL
+    assert probe(vp(A), vp(A), vp(0), 128, 10, 8, 1000, 0, 1, vp(A), None) == EINVAL
+    assert probe(vp(A), vp(A), vp(A), 0, 10, 8, 1000, 0, 1, vp(A), None) == EINVAL
+    assert probe(vp(A), vp(A), vp(A), 128, 10, 8, 1000, 2, 1, vp(A), None) == EINVAL       # unknown load pattern
+    assert probe(vp(ODD), vp(A), vp(A), 128, 10, 8, 1000, 0, 1, vp(A), None) == EINVAL
+    assert L.step_profile_begin(0) == EINVAL
+    ids = (ctypes.c_int32 * 4)(); ms = (ctypes.c_float * 4)()
+    assert L.step_profile_end(ids, ms, 4) == -EINVAL                                       # no session open
+    assert L.step_profile_kernel_name(2) == b"attn_partial" and L.step_profile_kernel_name(999) == b"unknown"
+    assert b"STEP_EFREELIST" in L.step_strerror(23)
+    assert binding.score_workspace_bytes(binding.ScoreDims(64, 4096, 16 * 1025, 4, 64, 0)) == 0    # m above 16384
+
