@@ -70,8 +70,9 @@ typedef struct {
 size_t step_attn_workspace_bytes(const step_attn_dims *dims);
 /* Wavefronts per KV head that stage 1 keeps resident on the current device for these dims (host
  * function; 0 on bad dims): (compute units x resident waves per unit) / Hkv.  The work is cut so
- * that each of them streams the same number of pages.  The environment variable
- * STEP_ATTN_WAVES_PER_CU, read once, overrides the occupancy query (tuning aid). */
+ * that each of them streams the same number of pages.  The streaming kernels are built for one wave
+ * per SIMD (four per compute unit).  The environment variable STEP_ATTN_WAVES_PER_CU, read once, overrides
+ * the count (tuning aid; more than four per unit run as a second round). */
 int32_t step_attn_waves_per_head(const step_attn_dims *dims);
 
 /*

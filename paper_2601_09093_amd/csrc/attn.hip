@@ -165,6 +165,8 @@ int run(const step_attn_dims *d, const uint16_t *q, const uint16_t *k_pages, con
     a.out = out; a.status = status;
     a.N = d->N; a.Hq = d->Hq; a.Hkv = d->Hkv; a.MAXB = d->MAXB; a.NP = d->NP;
     a.Wh = l.Wh; a.TB = l.TB; a.nblk = l.nblk; a.pmax = l.pmax; a.max_slots = l.max_slots;
+    a.prefix_base = 0;
+    a.priv_base = d->N * l.pmax;
     a.prefix_qt = l.prefix_qt;
     // never 0, so a cleared workspace never passes for a plan
     a.stamp = (int)((0x5157u ^ ((u32)d->N * 2654435761u) ^ ((u32)d->MAXB * 40503u) ^ ((u32)d->NP * 2246822519u) ^

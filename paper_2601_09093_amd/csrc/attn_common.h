@@ -9,11 +9,11 @@
 //             of the block and lie below every such trace's last full page (the prompt's pages; 0 when the
 //             block has fewer than two live traces).  It is found by one wave from the block's TB rows.
 //   Prefix.   The S_b shared pages of a block are cut into parts_b sub-chunks of sc_b pages (prefix_split);
-//             sub-chunk p of trace t is partial slot p * N + t (attn_front computes these).
+//             sub-chunk p of trace t is partial slot prefix_base + p * N + t (attn_front computes these).
 //   Private.  Trace t keeps priv_t = pages_t - S_b(t) private pages.  The private pages of all traces,
 //             concatenated in trace order, are cut into Wh runs of Q = ceil(total / Wh) pages, one per
 //             streaming wave of a KV head; the piece of trace t inside the run of wave wh is one record,
-//             partial slot N * pmax + base_t + (wh - first wave of t), base_t = pieces of the traces before t.
+//             partial slot priv_base + base_t + (wh - first wave of t), base_t = pieces of the traces before t.
 //   Every wave derives its own run from seq_lens and S_b with two prefix sums (plan_build): there is no
 //   planning kernel and no record array.
 #pragma once
@@ -53,7 +53,9 @@ struct AttnArgs {
     int32_t *status;
     int N, Hq, Hkv, MAXB, NP, Wh;
     int TB, nblk;         // traces per block, number of blocks
-    int pmax;             // sub-chunks of a shared prefix per trace at most (slots [0, N * pmax) are theirs)
+    int pmax;             // sub-chunks of a shared prefix per trace at most
+    int priv_base;        // first partial slot of the private-page records (N + Wh of them at most)
+    int prefix_base;      // first partial slot of the shared-prefix sub-chunks (N * pmax of them)
     int max_slots;        // partial slots the workspace holds: N * pmax + N + Wh
     int stamp;            // what hdr->stamp must hold when the per-block prefix lengths are taken from the workspace
     int prefix_qt;        // 16-row query tiles per wave of attn_front (1 or 2); 0: shared prefixes are not looked for
@@ -290,7 +292,7 @@ __device__ __forceinline__ void publish_plan(const AttnArgs &a, const WavePlan &
 {
     int slots = 0, smax = 0;
     for (int t = lane; t < a.N; t += 64) {
-        a.first2[t] = a.N * a.pmax + base_s[t];
+        a.first2[t] = a.priv_base + base_s[t];
         a.cnt2[t] = base_s[t + 1] - base_s[t];
         const int nb = pages_of(a.seq_lens[t], a.MAXB);
         const int S = nb - (P_s[t + 1] - P_s[t]);
@@ -357,7 +359,7 @@ struct RunWalker {
         r.first = S + (pos - p0);
         r.n = stop - pos;
         r.ntok = (r.first + r.n == nb) ? L - (nb - 1) * kPageTokens : kPageTokens;
-        r.slot = a.N * a.pmax + base_s[t] + (wh - p0 / Q);
+        r.slot = a.priv_base + base_s[t] + (wh - p0 / Q);
         pos = stop;
         if (pos >= end) {
             t = -1;

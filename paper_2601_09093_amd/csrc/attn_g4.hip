@@ -41,8 +41,12 @@ __device__ __forceinline__ void bfly_stage(float (&val)[NV], int c)
     }
 }
 
+// One wave per SIMD is part of the design (the work is cut into as many equal runs as there are SIMDs), so the
+// kernel asks for an occupancy of exactly one: the hardware then cannot put two of its waves on one SIMD and
+// leave another idle, which it otherwise sometimes did (seen as a 6 % longer kernel whenever the launch before
+// it had left the workgroup dispatcher in a different state, and as 0.7 % on average).
 template <int D>
-__global__ __launch_bounds__(64, 2) void attn_partial_g4(const AttnArgs a)
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_partial_g4(const AttnArgs a)
 {
     constexpr int G = 4;
     constexpr int LPR = D / 8, TPI = 64 / LPR, IPP = kPageTokens / TPI, NV = IPP * G;

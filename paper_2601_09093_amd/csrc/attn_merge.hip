@@ -23,11 +23,11 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
     prefix_split(a, clamp_shared(a, a.blk_shared[i / a.TB], nb), parts, sc);
     const int f2 = a.first2[i], c2 = a.cnt2[i];
     int nch = nb > 0 ? parts + c2 : 0;
-    if (nch > 0 && (c2 < 0 || f2 < a.N * a.pmax || (long long)f2 + c2 > a.max_slots)) {
+    if (nch > 0 && (c2 < 0 || f2 < a.priv_base || (long long)f2 + c2 > (long long)a.priv_base + a.N + a.Wh)) {
         if (lane == 0) report(a.status, STEP_EPLAN);
         nch = 0;
     }
-    auto slot_of = [&](int ch) { return (size_t)(ch < parts ? ch * a.N + i : f2 + (ch - parts)) * a.Hkv + g; };
+    auto slot_of = [&](int ch) { return (size_t)(ch < parts ? a.prefix_base + ch * a.N + i : f2 + (ch - parts)) * a.Hkv + g; };
 
     float o[DPT];
 #pragma unroll

@@ -290,7 +290,7 @@ __global__ __launch_bounds__(64) void attn_front(const AttnArgs a)
     // partials of the slots p * N + trace
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt)
-        MP::store_partial(a, ((size_t)p * a.N + trace_of[qt]) * a.Hkv + g, G, hh_of[qt], gr, valid[qt], m[qt], l[qt], o[qt]);
+        MP::store_partial(a, ((size_t)a.prefix_base + (size_t)p * a.N + trace_of[qt]) * a.Hkv + g, G, hh_of[qt], gr, valid[qt], m[qt], l[qt], o[qt]);
     if (bad_page && lane == 0) report(a.status, STEP_EPAGE);
 }
 
@@ -320,8 +320,8 @@ __global__ __launch_bounds__(64) void attn_plan_blocks(const AttnArgs a)
 // their use across record boundaries: the wave's page pairs form one sequence, a load cursor runs kBufs
 // pairs ahead of the compute cursor.
 // ---------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(64) void attn_partial_mfma(const AttnArgs a)
+template <int D>  // (one wave per SIMD, enforced: see attn_partial_g4)
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_partial_mfma(const AttnArgs a)
 {
     typedef MfmaPair<D> MP;
     constexpr int KB = MP::KB, DB = MP::DB;

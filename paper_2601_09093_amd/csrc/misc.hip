@@ -15,8 +15,9 @@ __global__ __launch_bounds__(256) void copy16(uint4 *__restrict__ dst, const uin
 // PATTERN 0: 1 KB contiguous per load instruction (the dot2 kernel's loads); 1: the matrix-core operand
 // pattern (K: 16 rows x 64 bytes, V: 4 rows x 256 bytes per instruction).  NT: non-temporal loads.
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+// (occupancy of exactly one wave per SIMD, like the streaming kernels it stands in for)
 template <int PATTERN, bool NT>
-__global__ __launch_bounds__(64) void read_probe(const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void read_probe(const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
                                                  const int32_t *__restrict__ ids, int pages_per_wave, int Hkv, int NP,
                                                  u32 *sink)
 {
