@@ -105,6 +105,49 @@ def test_running_mean_division_is_the_correctly_rounded_quotient():
     assert np.array_equal(scores, np.full(3, 0.5, np.float32))
 
 
+def test_calls_in_flight_on_several_streams_do_not_disturb_each_other():
+    """step_score hands sums from workgroup to workgroup through arrival counters that belong to the library; every
+    call takes the next of 64 counter sets.  Twelve calls of three different shapes are enqueued on twelve streams
+    without waiting in between, twice over; every result equals, bit for bit, the one the same call gives alone."""
+    shapes = [(4096, 1024, 4, 0), (4096, 512, 26, 0), (2560, 512, 13, 1)]
+    cases = []
+    for i in range(12):
+        d, m, B, act = shapes[i % 3]
+        N = max(B, 4)
+        sc = wl.build_scorer(9000 + i, N, N, d, m, B, act, prior_state=True)
+        t = dict(hidden=dev_bits(sc.hidden), bidx=dev(sc.boundary_idx), W1=dev_bits(sc.W1), b1=dev(sc.b1), W2=dev_bits(sc.W2),
+                 b2=torch.tensor([sc.b2], dtype=torch.float32, device=DEV), trace_of=dev(sc.trace_of), act=act, N=N,
+                 sum0=dev(sc.score_sum), cnt0=dev(sc.score_cnt))
+        t["ws"] = binding.new_workspace(binding.score_workspace_bytes(binding.ScoreDims(N, d, m, B, N, act)), DEV)
+        cases.append(t)
+
+    def run(t, st):
+        ssum, cnt = t["sum0"].clone(), t["cnt0"].clone()
+        scores = torch.empty(t["N"], dtype=torch.float32, device=DEV)
+        lo, pr = binding.step_score(t["hidden"], t["bidx"], t["W1"], t["b1"], t["W2"], t["b2"], act=t["act"],
+                                    trace_of=t["trace_of"], score_sum=ssum, score_cnt=cnt, scores=scores,
+                                    workspace=t["ws"], status=st)
+        return lo, pr, ssum, cnt, scores
+
+    st = new_status()
+    alone = []
+    for t in cases:
+        alone.append(run(t, st))
+        torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in cases]
+    for _ in range(2):
+        torch.cuda.synchronize()
+        got = []
+        for t, s in zip(cases, streams):
+            with torch.cuda.stream(s):
+                got.append(run(t, st))
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0
+        for a, b in zip(alone, got):
+            for x, y in zip(a, b):
+                assert torch.equal(x.view(torch.int32), y.view(torch.int32))
+
+
 def test_logits_only_without_state():
     s = wl.build_scorer(79, 4, 4, 512, 64, 3, 1)
     lo, pr, *_ = run_gpu(s, 4, with_state=False)
