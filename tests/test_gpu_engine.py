@@ -132,6 +132,60 @@ def test_free_list_is_kept_across_prune_free_and_reserve_calls():
     assert (sl > 0).sum() >= 1
 
 
+@pytest.mark.parametrize("seq", range(8))
+def test_random_sequences_on_one_free_list(seq):
+    """Random sequences of calls that free and take pages on one persistent workspace: reserve under pressure,
+    prune_free + step_freelist_add, and a change of the reference counts from outside followed by a rebuild; the
+    traces grow by random amounts in between.  After every call the state equals the oracle's."""
+    r = wl.rng_for(77000 + seq, 0)
+    N = int(r.choice([3, 8, 33, 64, 200]))
+    MAXB = 40
+    lens = 32 + r.integers(1, 200, N)
+    lay = wl.build_layout(lens, 32, P, wl.rng_for(77000 + seq, 1), slack=1.0, maxb=MAXB)
+    extra = int(r.integers(0, N))
+    NP = lay.NP + extra
+    perm = r.permutation(NP)
+    rc = np.empty(NP, np.int32); rc[perm] = np.concatenate([lay.refcounts, np.zeros(extra, np.int32)])
+    bt = np.where(lay.block_tables >= 0, perm[np.maximum(lay.block_tables, 0)], -1).astype(np.int32)
+    sl = lay.seq_lens.copy()
+    scores = r.random(N).astype(np.float32)
+    t_rc, t_bt, t_sl, t_sc = dev(rc), dev(bt), dev(sl), dev(scores)
+    st = new_status()
+    ws = binding.reserve_workspace(t_rc, N, MAXB)
+    for op in range(40):
+        live = np.nonzero(sl > 0)[0]
+        if live.size == 0:
+            break
+        kind = r.random()
+        if kind < 0.6:
+            pruned, n_pruned, new_pages = binding.reserve_pages(t_sc, t_rc, t_bt, t_sl, workspace=ws, status=st)
+            o_pruned, o_new = oracle.reserve_pages(scores, rc, bt, sl, P)
+            torch.cuda.synchronize()
+            assert pruned.cpu().numpy()[: int(n_pruned.item())].tolist() == o_pruned.tolist(), op
+            assert np.array_equal(new_pages.cpu().numpy()[:N], o_new), op
+            live = np.nonzero(sl > 0)[0]                              # the traces grow inside the pages they own
+            room = np.where(sl[live] % P == 0, np.where(o_new[live] >= 0, P, 0), P - sl[live] % P)
+            adv = np.minimum(room, r.integers(0, P + 1, live.size))
+            adv = np.where(sl[live] + adv > (MAXB - 1) * P, 0, adv)
+            sl[live] += adv.astype(np.int32)
+            t_sl.copy_(dev(sl))
+        elif kind < 0.85 and live.size > 1:
+            k = int(r.integers(1, max(2, live.size // 3)))
+            _, fr, nf = binding.prune_free(t_sc, k, t_rc, t_bt, t_sl, status=st)
+            binding.freelist_add(NP, fr, nf, ws, status=st)
+            oracle.prune_free(scores, k, rc, bt, sl, P)
+        else:
+            free = np.nonzero(rc == 0)[0]
+            if free.size:
+                rc[free[int(r.integers(0, free.size))]] = 1           # taken by someone else
+                t_rc.copy_(dev(rc))
+                binding.freelist_rebuild(t_rc, ws)
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0, (op, binding.ERROR_NAMES.get(int(st.item())))
+        assert np.array_equal(t_rc.cpu().numpy(), rc) and np.array_equal(t_bt.cpu().numpy(), bt), op
+        assert np.array_equal(t_sl.cpu().numpy(), sl), op
+
+
 def test_append_kv_bit_exact():
     lay = wl.build_layout(np.array([17, 32, 0, 5, 100, 48]), 0, P, wl.rng_for(6, 1), slack=1.5, maxb=8)
     Hkv, D = 8, 128
