@@ -154,9 +154,10 @@ size_t step_score_workspace_bytes(const step_score_dims *dims);
  * stay fp32.  logits within 1e-3 max-abs of the float64 definition.  m <= 16384.
  * One kernel launch: the workgroups that split W1 hand their sums over through `workspace` and through
  * arrival counters that belong to the library (device words that are zero between calls); every sum is
- * taken in a fixed order, so results are bit-identical from call to call.  Each call takes the next of 64
- * counter sets: calls on one stream, or up to 64 calls in flight on different streams of one GPU, do not
- * interfere; a call recorded in a HIP graph keeps the set it was recorded with.
+ * taken in a fixed order, so results are bit-identical from call to call.  Calls that may be in flight at
+ * the same time (different streams, replays of different recorded graphs) must be given different
+ * workspaces; the library keeps one counter set per workspace address, for the 64 most recently used
+ * addresses, so such calls do not interfere as long as no more than 64 scorer workspaces are in use.
  */
 int step_score(const step_score_dims *dims, const uint16_t *hidden, const int32_t *boundary_idx,
                const uint16_t *W1, const float *b1, const uint16_t *W2, const float *b2,

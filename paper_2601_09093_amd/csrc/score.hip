@@ -18,9 +18,10 @@
 // The split over d puts at least 256 workgroups on the W1 stream whatever m is (the paper's m = 512 gives only
 // 32 row tiles); every sum is taken in a fixed order, so the result does not depend on which workgroup arrives last.
 // The tickets are library-owned device words that start at zero and are put back to zero by the workgroup that
-// finds itself last; each call takes the next of kTicketSets sets, so calls that overlap on different streams
-// do not meet unless more than kTicketSets of them are in flight.
-#include <atomic>
+// finds itself last.  Calls that may be in flight together already have to use different workspaces (the chunk
+// sums live there), so a ticket set is kept per workspace address: such calls never meet, whether they are
+// issued directly or replayed from a recorded graph, unless more than kTicketSets workspaces are in use.
+#include <mutex>
 
 #include "common.h"
 
@@ -347,7 +348,30 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
     score_finish(a, prob_s, trace_s, sum_s, cnt_s);
 }
 
-std::atomic<unsigned> g_next_set{0};
+// ticket set of a workspace; with more than kTicketSets workspaces the one unused for longest gives up its set
+std::mutex g_set_mutex;
+struct SetSlot {
+    const void *workspace;
+    unsigned long long last_use;
+};
+SetSlot g_set_slots[kTicketSets];
+unsigned long long g_set_clock = 0;
+
+int ticket_set_of(const void *workspace)
+{
+    std::lock_guard<std::mutex> lock(g_set_mutex);
+    int oldest = 0;
+    for (int i = 0; i < kTicketSets; ++i) {
+        if (g_set_slots[i].workspace == workspace) {
+            g_set_slots[i].last_use = ++g_set_clock;
+            return i;
+        }
+        if (g_set_slots[i].last_use < g_set_slots[oldest].last_use) oldest = i;
+    }
+    g_set_slots[oldest].workspace = workspace;
+    g_set_slots[oldest].last_use = ++g_set_clock;
+    return oldest;
+}
 
 // chunks of the contraction over d: enough workgroups to stream W1 from the whole chip when there are few
 // row tiles and few boundaries
@@ -414,7 +438,7 @@ extern "C" int step_score(const step_score_dims *d, const uint16_t *hidden, cons
     const size_t MT = d->m / 16, Bp = d->B > 0 ? d->B : 1;
     a.plogit = reinterpret_cast<float *>(workspace);
     a.partial = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ((MT * Bp * sizeof(float) + 255) & ~(size_t)255));
-    a.set = (int)(g_next_set.fetch_add(1, std::memory_order_relaxed) % kTicketSets);
+    a.set = ticket_set_of(workspace);
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (d->B > 0) {

@@ -106,9 +106,11 @@ def test_running_mean_division_is_the_correctly_rounded_quotient():
 
 
 def test_calls_in_flight_on_several_streams_do_not_disturb_each_other():
-    """step_score hands sums from workgroup to workgroup through arrival counters that belong to the library; every
-    call takes the next of 64 counter sets.  Twelve calls of three different shapes are enqueued on twelve streams
-    without waiting in between, twice over; every result equals, bit for bit, the one the same call gives alone."""
+    """step_score hands sums from workgroup to workgroup through arrival counters that belong to the library, one
+    set of counters per workspace address.  Twelve calls of three different shapes, each with its own workspace,
+    are enqueued on twelve streams without waiting in between, six times over; every result equals, bit for bit,
+    the one the same call gives alone.  Then one call goes through seventy workspaces in turn -- more than the
+    library keeps sets for, so sets change hands -- with the same result every time."""
     shapes = [(4096, 1024, 4, 0), (4096, 512, 26, 0), (2560, 512, 13, 1)]
     cases = []
     for i in range(12):
@@ -135,7 +137,7 @@ def test_calls_in_flight_on_several_streams_do_not_disturb_each_other():
         alone.append(run(t, st))
         torch.cuda.synchronize()
     streams = [torch.cuda.Stream() for _ in cases]
-    for _ in range(2):
+    for _ in range(6):
         torch.cuda.synchronize()
         got = []
         for t, s in zip(cases, streams):
@@ -146,6 +148,15 @@ def test_calls_in_flight_on_several_streams_do_not_disturb_each_other():
         for a, b in zip(alone, got):
             for x, y in zip(a, b):
                 assert torch.equal(x.view(torch.int32), y.view(torch.int32))
+    t = dict(cases[1])
+    nbytes = binding.score_workspace_bytes(binding.ScoreDims(t["N"], 4096, 512, 26, t["N"], 0))
+    arena = binding.new_workspace(70 * ((nbytes + 255) // 256 * 256), DEV)
+    for i in range(70):
+        off = i * ((nbytes + 255) // 256 * 256)
+        t["ws"] = arena[off:off + nbytes]
+        for x, y in zip(alone[1], run(t, st)):
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32))
+    assert int(st.item()) == 0
 
 
 def test_logits_only_without_state():
