@@ -166,6 +166,23 @@ def test_documented_post_state_after_a_bad_page_id_or_reference_count(big):
     assert np.array_equal(o_rc, rc) and np.array_equal(o_bt, bt)      # the oracle's convention: nothing modified
 
 
+def test_stale_entries_behind_the_last_page_in_use_are_cleared_and_release_nothing():
+    """The hand case of the oracle's pins (the whole row becomes -1, entries behind ceil(L / P) release nothing),
+    and the same on a layout large enough for the three-launch path, with stale valid page ids behind every row."""
+    bt = np.array([[2, 0, 3, 1], [1, 4, -1, -1]], np.int32)
+    sl = np.array([20, 30], np.int32)
+    rc = np.array([1, 1, 1, 7, 1], np.int32)
+    pruned, freed, rc1, bt1, sl1 = run_gpu(np.array([0.1, 0.9], np.float32), 1, rc, bt, sl)
+    assert pruned.tolist() == [0] and freed.tolist() == [0, 2]
+    assert bt1.tolist() == [[-1, -1, -1, -1], [1, 4, -1, -1]] and sl1.tolist() == [0, 30] and rc1.tolist() == [0, 1, 0, 7, 1]
+    lay = _layout(91, 96, 64, 200, 4000)
+    r = wl.rng_for(91, 5)
+    for i in range(96):
+        nb = (lay.seq_lens[i] + P - 1) // P
+        lay.block_tables[i, nb:] = r.integers(0, lay.NP, lay.MAXB - nb)
+    check(wl.rng_for(91, 2).uniform(0, 1, 96).astype(np.float32), 40, lay)
+
+
 def test_host_reported_errors():
     lay = _layout(43, 4, 0, 20, 60)
     scores = dev(np.zeros(4, np.float32))

@@ -186,3 +186,14 @@ def test_errors():
     assert e.value.name == "ELEN"
     with pytest.raises(oracle.OracleError):   # Hq not a multiple of Hkv
         oracle.paged_decode_attn(q[:, :3].copy(), k, v, lay.block_tables, lay.seq_lens)
+    # two different mistakes: the one in the earlier (trace, head) row is the one reported
+    bt = lay.block_tables.copy(); bt[2, 0] = lay.NP
+    sl = lay.seq_lens.copy(); sl[0] = -1
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.paged_decode_attn(q, k, v, bt, sl)
+    assert e.value.name == "ELEN"
+    sl = lay.seq_lens.copy(); sl[2] = -1
+    bt = lay.block_tables.copy(); bt[0, 0] = lay.NP
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.paged_decode_attn(q, k, v, bt, sl)
+    assert e.value.name == "EPAGE"

@@ -106,6 +106,31 @@ def test_errors_leave_state_untouched():
     rc = np.concatenate([lay.refcounts, np.zeros(2, np.int32)])
     pruned, new = oracle.reserve_pages(sc, rc, bt, sl, P)    # no pruning needed: NaN is never looked at
     assert pruned.size == 0 and (new >= 0).all()
+    # a full pool, three traces at a page boundary, trace 1 has the lowest score: what is wrong with trace 1's
+    # pages is reported and nothing changes
+    lay = _layout(11, [32, 32, 32], maxb=4)
+    sc = np.array([0.6, 0.2, 0.8], np.float32)
+    for mutate, name in [
+        (lambda rc, bt, sl: bt.__setitem__((1, 1), lay.NP), "EPAGE"),
+        (lambda rc, bt, sl: bt.__setitem__((1, 0), -1), "EPAGE"),
+        (lambda rc, bt, sl: rc.__setitem__(bt[1, 1], 0), "EREFCOUNT"),
+        (lambda rc, bt, sl: sl.__setitem__(2, -1), "ELEN"),
+        (lambda rc, bt, sl: sl.__setitem__(0, 4 * P + 1), "ELEN"),
+    ]:
+        rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+        mutate(rc, bt, sl)
+        rc0, bt0, sl0 = rc.copy(), bt.copy(), sl.copy()
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.reserve_pages(sc, rc, bt, sl, P)
+        assert e.value.name == name
+        assert np.array_equal(rc, rc0) and np.array_equal(bt, bt0) and np.array_equal(sl, sl0)
+    # the score of a trace that is already gone is never looked at, also under pressure: two free pages for
+    # three traces at a page boundary
+    lay = _layout(12, [32, 32, 32, 32], maxb=4)
+    rc, bt, sl = lay.refcounts.copy(), lay.block_tables.copy(), lay.seq_lens.copy()
+    rc[bt[0, :2]] = 0; bt[0] = -1; sl[0] = 0
+    pruned, new = oracle.reserve_pages(np.array([np.nan, 0.2, 0.8, 0.5], np.float32), rc, bt, sl, P)
+    assert pruned.tolist() == [1] and new[0] == -1 and new[1] == -1 and (new[2:] >= 0).all()
 
 
 def test_append_writes_exactly_one_row_per_live_trace():
@@ -163,6 +188,15 @@ def test_append_errors():
     with pytest.raises(oracle.OracleError) as e:
         oracle.append_kv(kn, kn, k, v, lay.block_tables, None, sl)
     assert e.value.name == "ELEN"
+    bt = lay.block_tables.copy(); bt[1, 1] = lay.NP          # one past the pool
+    sl = np.array([0, 20], np.int32)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.append_kv(kn, kn, k, v, bt, None, sl)
+    assert e.value.name == "EPAGE" and sl.tolist() == [0, 20] and not k.any()
+    # without reference counts nothing is checked about sharing: the row is written
+    sl = np.array([0, 20], np.int32)
+    oracle.append_kv(kn, kn, k, v, lay.block_tables, None, sl)
+    assert sl.tolist() == [0, 21] and (k[lay.block_tables[1, 1], 0, 4] == 1).all() and k.sum() == D
 
 
 def test_weighted_vote_hand_cases():
@@ -170,6 +204,7 @@ def test_weighted_vote_hand_cases():
     s = np.array([0.25, 0.5, 0.5, 9.0, 0.125, 0.7], np.float32)
     assert oracle.weighted_vote(a, s) == (7, 0.75)           # 7: 0.75, 3: 0.625, 9: 0.7; the -1 trace has no vote
     assert oracle.weighted_vote(np.array([5, 2], np.int32), np.array([0.5, 0.5], np.float32)) == (2, 0.5)  # tie
+    assert oracle.weighted_vote(np.array([2, 5], np.int32), np.array([0.5, 0.5], np.float32)) == (2, 0.5)  # tie
     assert oracle.weighted_vote(np.array([-1, -1], np.int32), np.array([0.5, 0.5], np.float32))[0] == -1
     assert oracle.weighted_vote(np.zeros(0, np.int32), np.zeros(0, np.float32))[0] == -1
     # one confident trace outweighs two weak ones: majority by weight, not by count

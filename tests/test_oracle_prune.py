@@ -129,6 +129,8 @@ def test_errors_leave_state_untouched():
         (lambda rc, bt, sl, sc: bt.__setitem__((int(np.argmin(sc)), 1), lay.NP), "EPAGE"),
         (lambda rc, bt, sl, sc: rc.__setitem__(bt[int(np.argmin(sc)), 3], 0), "EREFCOUNT"),
         (lambda rc, bt, sl, sc: sl.__setitem__(0, lay.MAXB * P + 1), "ELEN"),
+        (lambda rc, bt, sl, sc: sl.__setitem__(7, -1), "ELEN"),
+        (lambda rc, bt, sl, sc: bt.__setitem__((int(np.argmin(sc)), 2), -1), "EPAGE"),
     ]:
         rc = lay.refcounts.copy(); bt = lay.block_tables.copy(); sl = lay.seq_lens.copy(); sc = scores.copy()
         mutate(rc, bt, sl, sc)
@@ -140,6 +142,14 @@ def test_errors_leave_state_untouched():
     with pytest.raises(oracle.OracleError) as e:           # k larger than the live set
         _run(lay, scores, 9)
     assert e.value.name == "EINVAL"
+    # ... also when k <= N: seven live traces of eight cannot lose eight
+    rc = lay.refcounts.copy(); bt = lay.block_tables.copy(); sl = lay.seq_lens.copy()
+    rc[bt[5][bt[5] >= 0]] -= 1; bt[5] = -1; sl[5] = 0
+    rc0, bt0, sl0 = rc.copy(), bt.copy(), sl.copy()
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.prune_free(scores, 8, rc, bt, sl, P)
+    assert e.value.name == "EINVAL"
+    assert np.array_equal(rc, rc0) and np.array_equal(bt, bt0) and np.array_equal(sl, sl0)
     # a NaN on a dead trace is ignored
     sc = scores.copy(); sc[4] = np.nan
     sl = lay.seq_lens.copy(); sl[4] = 0
@@ -153,3 +163,15 @@ def test_duplicate_page_in_one_row_is_released_once_per_reference():
     rc = np.array([2, 1, 5], np.int32)
     pruned, freed = oracle.prune_free(np.array([0.5], np.float32), 1, rc, bt, sl, P)
     assert pruned.tolist() == [0] and freed.tolist() == [0, 1] and rc.tolist() == [0, 0, 5]
+
+
+def test_whole_row_is_cleared_also_behind_the_last_page_in_use():
+    """T <- T \\ {t*} (Algorithm 1) leaves nothing of the trace: every entry of its block-table row becomes
+    -1, stale entries behind ceil(L / P) included, and those stale entries release nothing."""
+    bt = np.array([[2, 0, 3, 1], [1, 4, -1, -1]], np.int32)   # trace 0 uses 2 pages (L = 20); 3 and 1 are stale
+    sl = np.array([20, 30], np.int32)
+    rc = np.array([1, 1, 1, 7, 1], np.int32)
+    pruned, freed = oracle.prune_free(np.array([0.1, 0.9], np.float32), 1, rc, bt, sl, P)
+    assert pruned.tolist() == [0] and freed.tolist() == [0, 2]
+    assert bt.tolist() == [[-1, -1, -1, -1], [1, 4, -1, -1]] and sl.tolist() == [0, 30]
+    assert rc.tolist() == [0, 1, 0, 7, 1]

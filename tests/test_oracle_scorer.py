@@ -121,6 +121,15 @@ def test_boundary_index_errors():
         assert e.value.name == "EINDEX"
     lo, pr = oracle.step_score(s.hidden, np.zeros(0, np.int32), s.W1, s.b1, s.W2, s.b2)
     assert lo.size == 0 and pr.size == 0
+    for act in (-1, 2):                                     # only the two named activations exist
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.step_score(s.hidden, np.array([0], np.int32), s.W1, s.b1, s.W2, s.b2, act=act)
+        assert e.value.name == "EINVAL"
+    for bad in (-1, 3):                                     # a boundary of a trace that does not exist
+        sm, cn = np.ones(3, np.float32), np.ones(3, np.int32)
+        with pytest.raises(oracle.OracleError) as e:
+            oracle.running_mean(np.array([1, bad], np.int32), np.array([0.5, 0.5], np.float32), sm, cn)
+        assert e.value.name == "EINDEX" and sm.tolist() == [1, 1, 1] and cn.tolist() == [1, 1, 1]
 
 
 def test_running_mean_hand_cases():
