@@ -107,7 +107,8 @@ def main():
     import numpy as np
     import torch
 
-    from paper_2601_09093_amd import binding, workloads as wl
+    from paper_2601_09093_amd import binding, build as hip_build, workloads as wl
+    hip_build.ensure_built()  # builds only a tree that has never been built
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; libstep has no CPU path", file=sys.stderr)

@@ -40,5 +40,11 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build the library only if none is there (tests, the smoke run and the bench call this; a library that
+    exists is loaded as it is, so after a change to a source build again)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

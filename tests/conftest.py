@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # a tree that has never been built (a fresh clone) is built once; a built library is used as it is
+    from paper_2601_09093_amd import build as hip_build
+    hip_build.ensure_built()
+
+
 def pytest_collection_modifyitems(config, items):
     # GPU tests are skipped, not failed, where no device is visible.
     try:
