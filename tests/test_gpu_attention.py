@@ -427,6 +427,29 @@ def test_one_plan_shared_by_several_layers():
         assert np.array_equal(host_bits(one), host_bits(outs[l]))
 
 
+@pytest.mark.parametrize("D,Hq,Hkv,N", [(64, 2, 2, 12), (64, 16, 2, 40), (128, 4, 2, 20), (128, 16, 2, 40)])
+def test_planned_form_on_every_kernel_variant(D, Hq, Hkv, N):
+    """The planned form (prefix lengths read from the workspace instead of searched) on the shapes the one-plan test
+    does not reach: head dimension 64, one and two query tiles per wave of the shared-prefix kernel (N * G below
+    and above 256), the matrix-core streaming kernel.  Same bar as the one-call form and the same bits."""
+    r = wl.rng_for(7700 + D + N, 0)
+    lens = 96 + r.integers(1, 700, N); lens[3] = 0
+    lay, q, k, v = build(7700 + D + N, lens, Hq, Hkv, D, prompt=96)
+    tq, tk, tv, bt, sl = dev_bits(q), dev_bits(k), dev_bits(v), dev(lay.block_tables), dev(lay.seq_lens)
+    ws = binding.new_workspace(binding.attn_workspace_bytes(
+        binding.AttnDims(N, Hq, Hkv, D, P, lay.MAXB, lay.NP, D ** -0.5)), DEV)
+    st = new_status()
+    binding.attn_plan(tq, tk, bt, sl, ws, status=st)
+    out = torch.empty_like(tq)
+    binding.paged_decode_attn_planned(tq, tk, tv, bt, sl, out, ws, status=st)
+    one = binding.paged_decode_attn(tq, tk, tv, bt, sl, status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    want = oracle.paged_decode_attn(q, k, v, lay.block_tables, lay.seq_lens)
+    assert np.abs(host_f32_of_bf16(out) - want).max() <= TOL
+    assert np.array_equal(host_bits(one), host_bits(out))
+
+
 @pytest.mark.parametrize("fill", [0, 0x7F, "other_dims"])
 def test_attend_without_a_matching_plan_is_reported_not_followed(fill):
     """paged_decode_attn_planned on a workspace that holds no plan for these dims (cleared, garbage,
