@@ -58,6 +58,18 @@ def test_scorer_shapes(d, m, B, act):
     check(s, N)
 
 
+@pytest.mark.parametrize("d,m,B,N,R", [(256, 64, 2500, 3000, 400), (256, 64, 1025, 2049, 64), (128, 16384, 3, 4, 3),
+                                       (128, 16384, 40, 7, 40)])
+def test_sizes_beyond_what_is_staged_on_chip(d, m, B, N, R):
+    """More boundaries than the finishing workgroup stages at a time (1024), more traces than it keeps the running
+    state on chip for (2048), several boundaries per trace across those stages (the order of the fp32 sums must
+    survive), and the widest hidden layer the call takes (m = 16384: 1024 row tiles)."""
+    s = wl.build_scorer(600 + B + m, N, R, d, m, B, 0, prior_state=True, distinct_rows=False)
+    s.trace_of = wl.rng_for(600 + B, 50).integers(0, min(N, 97), B).astype(np.int32)   # many boundaries per trace
+    s.trace_of[-1] = N - 1
+    check(s, N)
+
+
 def test_duplicate_rows_and_repeated_traces_in_order():
     s = wl.build_scorer(77, 6, 10, 256, 64, 40, 0, distinct_rows=False)
     s.trace_of = (wl.rng_for(77, 50).integers(0, 6, 40)).astype(np.int32)
