@@ -183,6 +183,26 @@ def test_stale_entries_behind_the_last_page_in_use_are_cleared_and_release_nothi
     check(wl.rng_for(91, 2).uniform(0, 1, 96).astype(np.float32), 40, lay)
 
 
+@pytest.mark.parametrize("NP", [262143, 262144, 262145, 300000])
+def test_pool_sizes_around_the_single_launch_limit(NP):
+    """The single-launch path keeps the freed-page bitmap on chip for pools of up to 262144 pages; one page more
+    goes to the three-launch path.  A small batch scattered over such a pool, its last page included."""
+    lay = _layout(93, 40, 32, 100, 900)
+    r = wl.rng_for(93, 7)
+    spread = r.choice(NP - 1, lay.NP, replace=False).astype(np.int32)
+    spread[lay.block_tables[0, 3]] = NP - 1                  # a private page of trace 0, which is pruned first
+    rc = np.zeros(NP, np.int32); rc[spread] = lay.refcounts
+    bt = np.where(lay.block_tables >= 0, spread[np.maximum(lay.block_tables, 0)], -1).astype(np.int32)
+    scores = wl.rng_for(93, 2).uniform(0, 1, 40).astype(np.float32)
+    scores[0] = -1.0
+    got = run_gpu(scores, 9, rc, bt, lay.seq_lens)
+    rc2, bt2, sl2 = rc.copy(), bt.copy(), lay.seq_lens.copy()
+    pruned, freed = oracle.prune_free(scores, 9, rc2, bt2, sl2, P)
+    assert pruned[0] == 0 and freed[-1] == NP - 1
+    for name, a, b in zip(("pruned", "freed", "refcounts", "block_tables", "seq_lens"), got, (pruned, freed, rc2, bt2, sl2)):
+        assert np.array_equal(a, b), name
+
+
 def test_host_reported_errors():
     lay = _layout(43, 4, 0, 20, 60)
     scores = dev(np.zeros(4, np.float32))
