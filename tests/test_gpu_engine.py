@@ -77,6 +77,23 @@ def test_reserve_pages_config5_scale_saturated_pool():
     assert (new >= 0).sum() > 0
 
 
+def test_reserve_pages_most_traces_a_call_takes_under_pressure():
+    """N = 4096 traces, a third of them at a page boundary, a pool with only a few free pages: many rounds of
+    the trigger (prune the lowest, re-check) before everybody that is left gets a page."""
+    r = wl.rng_for(720, 0)
+    N = 4096
+    lens = 16 + 16 * r.integers(0, 4, N) + np.where(r.random(N) < 0.33, 0, r.integers(1, 16, N))
+    lens[r.random(N) < 0.05] = 0
+    lay = wl.build_layout(lens, 16, P, wl.rng_for(720, 1), slack=1.0, maxb=6)
+    rc = np.concatenate([lay.refcounts, np.zeros(900, np.int32)])
+    perm = wl.rng_for(720, 2).permutation(rc.size)
+    rc2 = np.empty_like(rc); rc2[perm] = rc
+    bt = np.where(lay.block_tables >= 0, perm[np.maximum(lay.block_tables, 0)], -1).astype(np.int32)
+    scores = (r.integers(0, 400, N) / 512.0).astype(np.float32)      # many ties
+    pruned, new, *_ = check_reserve(scores, rc2, bt, lay.seq_lens)
+    assert pruned.size > 50 and (new >= 0).sum() > 900
+
+
 def test_reserve_pages_errors():
     lay = wl.build_layout(np.array([32, 32]), 0, P, wl.rng_for(4, 1), maxb=2)
     gpu_reserve(np.zeros(2, np.float32), lay.refcounts, lay.block_tables, lay.seq_lens, expect_status=17)
@@ -228,6 +245,20 @@ def test_weighted_vote_bit_exact():
         assert int(st.item()) == 0 and int(w.item()) == ow and np.float32(wt.item()) == np.float32(owt)
     w, _ = binding.weighted_vote(dev(np.full(5, -1, np.int32)), dev(np.ones(5, np.float32)))
     assert int(w.item()) == -1
+    # the most traces a call takes, answer ids anywhere in the int32 range, exact ties between answers
+    N = 4096
+    ids = np.array([0, 1, 17, 2 ** 31 - 2, 2 ** 31 - 1, 123456789, 5, 6], np.int64)
+    a = ids[r.integers(0, ids.size, N)].astype(np.int32)
+    a[r.random(N) < 0.2] = -1
+    s = (r.integers(1, 9, N) / 8.0).astype(np.float32)                # dyadic: sums are exact, ties do happen
+    st = new_status()
+    w, wt = binding.weighted_vote(dev(a), dev(s), status=st)
+    torch.cuda.synchronize()
+    ow, owt = oracle.weighted_vote(a, s)
+    assert int(st.item()) == 0 and int(w.item()) == ow and np.float32(wt.item()) == np.float32(owt)
+    a2 = np.array([2 ** 31 - 1, 7, 2 ** 31 - 1, 7], np.int32); s2 = np.array([0.5, 0.25, 0.25, 0.5], np.float32)
+    w, wt = binding.weighted_vote(dev(a2), dev(s2))
+    assert (int(w.item()), float(wt.item())) == oracle.weighted_vote(a2, s2) == (7, 0.75)
 
 
 def _decode_loop(NP):
