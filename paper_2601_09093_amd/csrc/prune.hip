@@ -23,6 +23,25 @@ typedef unsigned long long u64;
 constexpr int kSelThreads = 1024;
 static_assert(kSelThreads == 1024, "block_excl_scan works on 1024-thread workgroups");
 constexpr int kMaxN = 4096;
+constexpr int kRankN = 256;  // up to this many keys are ordered by counting, not by sorting
+
+// Few keys: the place of a live key among the selected is the number of smaller keys (keys are distinct, the trace
+// index is part of them; the keys of dead traces are all ~0 and are not placed).  Every thread reads all npad keys as
+// LDS broadcasts -- no exchange stages, no barriers in between.  On return keys[0 .. live) is ascending.
+__device__ __forceinline__ void order_by_counting(u64 *keys, int npad)
+{
+    const int tid = threadIdx.x;
+    const u64 mine = tid < npad ? keys[tid] : ~0ull;
+    int rank = 0;
+    if (mine != ~0ull) {
+        for (int j = 0; j < npad; j += 4) {  // (npad is a power of two, at least 4)
+            rank += (keys[j] < mine) + (keys[j + 1] < mine) + (keys[j + 2] < mine) + (keys[j + 3] < mine);
+        }
+    }
+    __syncthreads();
+    if (mine != ~0ull) keys[rank] = mine;
+    __syncthreads();
+}
 
 struct PruneHeader {  // first 256 bytes of the workspace
     int32_t k_eff;    // number of traces actually pruned (0 after a selection error)
@@ -77,8 +96,10 @@ __global__ __launch_bounds__(kSelThreads) void prune_select(const PruneArgs a)
         }
         return;
     }
-    // bitonic sort, ascending
-    if (a.npad <= kSelThreads) {
+    // ascending order of the keys: by counting when they are few, else a bitonic sort
+    if (a.npad <= kRankN) {
+        order_by_counting(keys, a.npad);
+    } else if (a.npad <= kSelThreads) {
         // one key per thread; exchanges at distance < 64 stay inside a wavefront (shuffles), larger
         // distances go through LDS
         u64 key = tid < a.npad ? keys[tid] : ~0ull;
@@ -233,8 +254,10 @@ __global__ __launch_bounds__(kSelThreads) void prune_fused(const PruneArgs a)
         }
         return;
     }
-    // bitonic sort, ascending: one key per thread
-    {
+    // ascending order of the keys: by counting when they are few, else a bitonic sort with one key per thread
+    if (a.npad <= kRankN) {
+        order_by_counting(keys, a.npad);
+    } else {
         u64 key = keys[tid];
         for (int size = 2; size <= a.npad; size <<= 1) {
             const bool asc = (tid & size) == 0;
@@ -353,7 +376,7 @@ int run_prune(int32_t N, int32_t MAXB, int32_t NP, int32_t P, const float *score
     a.hdr = reinterpret_cast<PruneHeader *>(scratch);
     a.bitmap = reinterpret_cast<u32 *>(reinterpret_cast<char *>(scratch) + 256);
     a.N = N; a.MAXB = MAXB; a.NP = NP; a.P = P; a.k = k;
-    a.npad = 2;
+    a.npad = 4;
     while (a.npad < N) a.npad <<= 1;
     a.words = (int)(((size_t)NP + 31) / 32);
 
