@@ -12,9 +12,9 @@
 //   3. applies bias and activation, multiplies by the 16 matching entries of W2 and stores one partial logit
 //      per boundary.
 //   4. the last workgroup of the launch to arrive adds the partial logits in tile order, applies the sigmoid,
-//      then one thread replays the boundaries in index order to update (sum, count) per trace -- fp32 addition
-//      is not associative and a trace may own several boundaries, so the order is part of the result -- and
-//      the scores are refreshed.
+//      then updates (sum, count) per trace with the trace's boundaries in index order -- fp32 addition is not
+//      associative and a trace may own several boundaries, so the order is part of the result; different traces
+//      do not meet and are replayed by different threads -- and the scores are refreshed.
 // The split over d puts at least 256 workgroups on the W1 stream whatever m is (the paper's m = 512 gives only
 // 32 row tiles); every sum is taken in a fixed order, so the result does not depend on which workgroup arrives last.
 // The tickets are library-owned device words that start at zero and are put back to zero by the workgroup that
@@ -67,6 +67,19 @@ __device__ __forceinline__ float ld_dev(const float *p)
 {
     return __hip_atomic_load(const_cast<float *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// two neighbouring floats (8-byte aligned) as one access
+typedef unsigned long long u64;
+__device__ __forceinline__ void st_dev2(float *p, float x, float y)
+{
+    const u64 v = (u64)__float_as_uint(x) | ((u64)__float_as_uint(y) << 32);
+    __hip_atomic_store(reinterpret_cast<u64 *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void ld_dev2(const float *p, float &x, float &y)
+{
+    const u64 v = __hip_atomic_load(reinterpret_cast<u64 *>(const_cast<float *>(p)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    x = __uint_as_float((u32)v);
+    y = __uint_as_float((u32)(v >> 32));
+}
 
 // true in every thread of the workgroup that is the last of `expected` to take the ticket; that workgroup
 // puts the ticket back to zero.  Every thread first waits until its own device-scope stores have been
@@ -84,6 +97,45 @@ __device__ __forceinline__ bool last_to_arrive(int32_t *ticket, int expected, in
     }
     __syncthreads();
     return *flag_s != 0;
+}
+
+// Logits and probabilities of the boundaries base + bb0 .. + KB4 (one wave): lane l adds the row tiles l, l + 64, ...
+// in ascending order, then the lanes are added pairwise (xor 32, 16, ... 1) -- the same order whatever KB4 is.
+template <int KB4>
+__device__ __forceinline__ void partial_logits(const ScoreArgs &a, int base, int nbd, int bb0, int lane, int mt, float b2,
+                                               float *prob_s)
+{
+    float acc[KB4];
+#pragma unroll
+    for (int u = 0; u < KB4; ++u) acc[u] = 0.f;
+    for (int t0 = 0; t0 < mt; t0 += 64 * 4) {
+        float v[4][KB4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int u = 0; u < KB4; ++u) {
+                const int t = t0 + r * 64 + lane, bb = bb0 + u;
+                v[r][u] = (t < mt && bb < nbd) ? ld_dev(&a.plogit[(size_t)t * a.B + base + bb]) : 0.f;
+            }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int u = 0; u < KB4; ++u) acc[u] += v[r][u];
+    }
+#pragma unroll
+    for (int u = 0; u < KB4; ++u) {
+        float x = acc[u];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+        const int bb = bb0 + u;
+        if (lane == 0 && bb < nbd) {
+            const float logit = b2 + x;
+            const float prob = 1.0f / (1.0f + expf(-logit));
+            a.logits[base + bb] = logit;
+            a.probs[base + bb] = prob;
+            prob_s[bb] = prob;
+        }
+    }
 }
 
 // step 4 (also the whole kernel when B == 0): logits, probabilities, running mean, scores
@@ -124,62 +176,53 @@ __device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, fl
     const int lane = tid & 63, wv = tid >> 6;
     for (int base = 0; base < a.B; base += kFinishChunk) {
         const int nbd = min(kFinishChunk, a.B - base);
-        // logit of a boundary = b2 + sum over the row tiles of its partial logits, in a fixed order: lane l adds the
-        // tiles l, l + 64, ... in ascending order, then the lanes are added pairwise (xor 32, 16, ... 1).  A wave takes
-        // four boundaries at a time so that their loads are in flight together.
-        constexpr int kB4 = 4;
-        for (int bb0 = wv * kB4; bb0 < nbd; bb0 += kWaves * kB4) {
-            float acc[kB4];
-#pragma unroll
-            for (int u = 0; u < kB4; ++u) acc[u] = 0.f;
-            for (int t0 = 0; t0 < mt; t0 += 64 * 4) {
-                float v[4][kB4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int u = 0; u < kB4; ++u) {
-                        const int t = t0 + r * 64 + lane, bb = bb0 + u;
-                        v[r][u] = (t < mt && bb < nbd) ? ld_dev(&a.plogit[(size_t)t * a.B + base + bb]) : 0.f;
-                    }
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int u = 0; u < kB4; ++u) acc[u] += v[r][u];
-            }
-#pragma unroll
-            for (int u = 0; u < kB4; ++u) {
-                float x = acc[u];
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
-                const int bb = bb0 + u;
-                if (lane == 0 && bb < nbd) {
-                    const float logit = b2 + x;
-                    const float prob = 1.0f / (1.0f + expf(-logit));
-                    a.logits[base + bb] = logit;
-                    a.probs[base + bb] = prob;
-                    prob_s[bb] = prob;
+        // logit of a boundary = b2 + sum over the row tiles of its partial logits, in a fixed order (partial_logits);
+        // a wave takes four boundaries at a time, eight when there are more than 16, so that their loads are in
+        // flight together and the boundaries of a call take one round
+        if (nbd > 16) {
+            for (int bb0 = wv * 8; bb0 < nbd; bb0 += kWaves * 8) partial_logits<8>(a, base, nbd, bb0, lane, mt, b2, prob_s);
+        } else {
+            for (int bb0 = wv * 4; bb0 < nbd; bb0 += kWaves * 4) partial_logits<4>(a, base, nbd, bb0, lane, mt, b2, prob_s);
+        }
+        // the boundaries' traces, padded with -1 to a multiple of four (they are read four at a time below)
+        for (int bb = tid; bb < ((nbd + 3) & ~3); bb += kThreads) {
+            int t = -1;
+            if (state && bb < nbd) {
+                t = a.trace_of[base + bb];
+                if ((u32)t >= (u32)a.N) {
+                    report(a.status, STEP_EINDEX);
+                    t = -1;
                 }
             }
+            trace_s[bb] = t;
         }
-        for (int bb = tid; bb < nbd; bb += kThreads) trace_s[bb] = state ? a.trace_of[base + bb] : 0;
         if (!state) continue;  // uniform
         park_state();
         __syncthreads();
-        if (tid == 0) {
-            // boundaries in index order: fp32 addition is not associative and a trace may own several
+        // A trace's sum takes its boundaries in index order: fp32 addition is not associative and a trace may own
+        // several.  Different traces do not meet, so with the state on chip every thread replays, for its own
+        // traces, the whole list (LDS broadcasts); otherwise one thread walks the list once.
+        if (staged) {
+            const int4 *tr4 = reinterpret_cast<const int4 *>(trace_s);
+            for (int t = tid; t < a.N; t += kThreads) {
+                float sm = sum_s[t];
+                int n = cnt_s[t];
+                for (int q4 = 0; q4 < (nbd + 3) / 4; ++q4) {
+                    const int4 tt = tr4[q4];
+                    if (tt.x == t) { sm = sm + prob_s[4 * q4 + 0]; ++n; }
+                    if (tt.y == t) { sm = sm + prob_s[4 * q4 + 1]; ++n; }
+                    if (tt.z == t) { sm = sm + prob_s[4 * q4 + 2]; ++n; }
+                    if (tt.w == t) { sm = sm + prob_s[4 * q4 + 3]; ++n; }
+                }
+                sum_s[t] = sm;
+                cnt_s[t] = n;
+            }
+        } else if (tid == 0) {
             for (int bb = 0; bb < nbd; ++bb) {
                 const int t = trace_s[bb];
-                if ((u32)t >= (u32)a.N) {
-                    report(a.status, STEP_EINDEX);
-                    continue;
-                }
-                if (staged) {
-                    sum_s[t] = sum_s[t] + prob_s[bb];
-                    cnt_s[t] = cnt_s[t] + 1;
-                } else {
-                    a.score_sum[t] = a.score_sum[t] + prob_s[bb];
-                    a.score_cnt[t] = a.score_cnt[t] + 1;
-                }
+                if (t < 0) continue;
+                a.score_sum[t] = a.score_sum[t] + prob_s[bb];
+                a.score_cnt[t] = a.score_cnt[t] + 1;
             }
         }
         __syncthreads();
@@ -208,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
 {
     __shared__ float red[kWaves][kBT][4][64];
     __shared__ float prob_s[kFinishChunk];
-    __shared__ int trace_s[kFinishChunk];
+    __shared__ __attribute__((aligned(16))) int trace_s[kFinishChunk];  // read four at a time
     __shared__ float sum_s[kStateMax];
     __shared__ int cnt_s[kStateMax];
     __shared__ int flag_s;
@@ -309,8 +352,8 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
         // step 1 -> 2: store the chunk's sums; the tile's last chunk to arrive adds all of them in chunk order
         if (w < kBT && b < a.B) {
             float *dst = a.partial + (((size_t)chunk * MT + mt) * a.B + b) * 16 + kg * 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) st_dev(dst + i, z[i]);
+            st_dev2(dst, z[0], z[1]);
+            st_dev2(dst + 2, z[2], z[3]);
         }
         if (!last_to_arrive(&tickets[bz * MT + mt], a.nchunk, &flag_s)) return;
         if (w < kBT && b < a.B) {
@@ -322,8 +365,8 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
                 for (int u = 0; u < 8; ++u) {
                     const int ch = min(ch0 + u, a.nchunk - 1);
                     const float *src = a.partial + (((size_t)ch * MT + mt) * a.B + b) * 16 + kg * 4;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[u][i] = ld_dev(src + i);
+                    ld_dev2(src, v[u][0], v[u][1]);
+                    ld_dev2(src + 2, v[u][2], v[u][3]);
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
