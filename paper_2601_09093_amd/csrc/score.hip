@@ -99,8 +99,23 @@ __device__ __forceinline__ bool last_to_arrive(int32_t *ticket, int expected, in
     return *flag_s != 0;
 }
 
+// Sum over the 64 lanes in a fixed order, returned to every lane: within each row of 16 lanes with four DPP exchanges
+// (xor 1, xor 2, half mirror, mirror: no LDS round trips), then the four row sums in row order.
+__device__ __forceinline__ float wave_sum(float x)
+{
+    x += dpp<kDppXor1>(x);
+    x += dpp<kDppXor2>(x);
+    x += dpp<kDppHalfMirror>(x);
+    x += dpp<kDppRowMirror>(x);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return ((r0 + r1) + r2) + r3;
+}
+
 // Logits and probabilities of the boundaries base + bb0 .. + KB4 (one wave): lane l adds the row tiles l, l + 64, ...
-// in ascending order, then the lanes are added pairwise (xor 32, 16, ... 1) -- the same order whatever KB4 is.
+// in ascending order, then the lanes are added by wave_sum -- the same order whatever KB4 is.
 template <int KB4>
 __device__ __forceinline__ void partial_logits(const ScoreArgs &a, int base, int nbd, int bb0, int lane, int mt, float b2,
                                                float *prob_s)
@@ -124,9 +139,7 @@ __device__ __forceinline__ void partial_logits(const ScoreArgs &a, int base, int
     }
 #pragma unroll
     for (int u = 0; u < KB4; ++u) {
-        float x = acc[u];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+        const float x = wave_sum(acc[u]);
         const int bb = bb0 + u;
         if (lane == 0 && bb < nbd) {
             const float logit = b2 + x;
@@ -139,26 +152,44 @@ __device__ __forceinline__ void partial_logits(const ScoreArgs &a, int base, int
 }
 
 // step 4 (also the whole kernel when B == 0): logits, probabilities, running mean, scores
-__device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, float *sum_s, int *cnt_s)
+// What the finishing workgroup needs and nothing in the launch changes before it: the running-mean state (when it
+// is staged on chip), the traces of the first kFinishChunk boundaries and the output bias.  Every workgroup requests them when it
+// starts -- it may turn out to be the last -- so these cold loads are not on the path behind the last ticket.
+constexpr int kPer = kStateMax / kThreads;
+constexpr int kTrPer = kFinishChunk / kThreads;
+struct FinishInputs {
+    float b2;
+    float rs[kPer];
+    int rc[kPer];
+    int tr[kTrPer];
+};
+
+__device__ __forceinline__ void request_finish_inputs(const ScoreArgs &a, FinishInputs &f)
+{
+    const int tid = threadIdx.x;
+    const bool state = a.score_sum != nullptr;
+    const bool staged = state && a.N <= kStateMax;
+    f.b2 = a.b2[0];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int t = tid + u * kThreads;
+        f.rs[u] = (staged && t < a.N) ? a.score_sum[t] : 0.f;
+        f.rc[u] = (staged && t < a.N) ? a.score_cnt[t] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < kTrPer; ++u) {
+        const int bb = tid + u * kThreads;
+        f.tr[u] = (state && bb < a.B) ? a.trace_of[bb] : -1;
+    }
+}
+
+__device__ void score_finish(const ScoreArgs &a, const FinishInputs &f, float *prob_s, int *trace_s, float *sum_s, int *cnt_s)
 {
     const int tid = threadIdx.x;
     const int mt = a.m / 16;
-    const float b2 = a.b2[0];
+    const float b2 = f.b2;
     const bool state = a.score_sum != nullptr;
-    const bool staged = state && a.N <= kStateMax;  // keep the sequential replay off global memory
-    // the state is requested first and parked in LDS only after the partial logits of the first boundaries have
-    // been requested and summed, so the cold loads overlap
-    constexpr int kPer = kStateMax / kThreads;
-    float rs[kPer];
-    int rc[kPer];
-    if (staged) {
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-            const int t = tid + u * kThreads;
-            rs[u] = t < a.N ? a.score_sum[t] : 0.f;
-            rc[u] = t < a.N ? a.score_cnt[t] : 0;
-        }
-    }
+    const bool staged = state && a.N <= kStateMax;  // keep the replay off global memory
     bool parked = false;
     auto park_state = [&]() {
         if (staged && !parked) {
@@ -166,8 +197,8 @@ __device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, fl
             for (int u = 0; u < kPer; ++u) {
                 const int t = tid + u * kThreads;
                 if (t < a.N) {
-                    sum_s[t] = rs[u];
-                    cnt_s[t] = rc[u];
+                    sum_s[t] = f.rs[u];
+                    cnt_s[t] = f.rc[u];
                 }
             }
         }
@@ -185,16 +216,20 @@ __device__ void score_finish(const ScoreArgs &a, float *prob_s, int *trace_s, fl
             for (int bb0 = wv * 4; bb0 < nbd; bb0 += kWaves * 4) partial_logits<4>(a, base, nbd, bb0, lane, mt, b2, prob_s);
         }
         // the boundaries' traces, padded with -1 to a multiple of four (they are read four at a time below)
-        for (int bb = tid; bb < ((nbd + 3) & ~3); bb += kThreads) {
-            int t = -1;
-            if (state && bb < nbd) {
-                t = a.trace_of[base + bb];
-                if ((u32)t >= (u32)a.N) {
-                    report(a.status, STEP_EINDEX);
-                    t = -1;
+#pragma unroll
+        for (int u = 0; u < kTrPer; ++u) {
+            const int bb = tid + u * kThreads;
+            if (bb < ((nbd + 3) & ~3)) {
+                int t = -1;
+                if (state && bb < nbd) {
+                    t = base == 0 ? f.tr[u] : a.trace_of[base + bb];
+                    if ((u32)t >= (u32)a.N) {
+                        report(a.status, STEP_EINDEX);
+                        t = -1;
+                    }
                 }
+                trace_s[bb] = t;
             }
-            trace_s[bb] = t;
         }
         if (!state) continue;  // uniform
         park_state();
@@ -255,8 +290,10 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
     __shared__ float sum_s[kStateMax];
     __shared__ int cnt_s[kStateMax];
     __shared__ int flag_s;
+    FinishInputs fin;
+    request_finish_inputs(a, fin);
     if (a.B == 0) {  // nothing to score: the scores are refreshed from the state
-        score_finish(a, prob_s, trace_s, sum_s, cnt_s);
+        score_finish(a, fin, prob_s, trace_s, sum_s, cnt_s);
         return;
     }
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -388,7 +425,7 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
     }
     // step 4
     if (!last_to_arrive(&tickets[kTicketsPerSet - 1], (int)(MT * gridDim.z), &flag_s)) return;
-    score_finish(a, prob_s, trace_s, sum_s, cnt_s);
+    score_finish(a, fin, prob_s, trace_s, sum_s, cnt_s);
 }
 
 // ticket set of a workspace; with more than kTicketSets workspaces the one unused for longest gives up its set
