@@ -62,9 +62,6 @@ struct AttnArgs {
     float scale_log2;     // scale * log2(e)
 };
 
-// max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
-__device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
-
 // Wave-uniform reads of data that no kernel of the same launch writes (block-table entries, lengths):
 // through the constant address space they become scalar loads, which have a counter of their own and
 // so do not queue behind the vector loads of the tile stream.

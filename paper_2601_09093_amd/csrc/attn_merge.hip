@@ -43,9 +43,7 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
             mp = ml[0];
             lp = ml[1];
         }
-        float Mn = mp;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) Mn = fmaxf(Mn, __shfl_xor(Mn, off));
+        float Mn = wave_max(mp);
         Mn = fmaxf(Mn, M);
         const float resc = __builtin_amdgcn_exp2f(M - Mn);
         M = Mn;
@@ -53,17 +51,14 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
 #pragma unroll
         for (int t = 0; t < DPT; ++t) o[t] *= resc;
         const float fp = __builtin_amdgcn_exp2f(mp - M);  // 0 for lanes without a piece
-        float lsum = fp * lp;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) lsum += __shfl_xor(lsum, off);
-        den += lsum;
+        den += wave_sum(fp * lp);
         int p = 0;
         for (; p + 3 < cnt; p += 4) {
             float v[4][DPT], f[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float *pa = a.part_acc + slot_of(base + p + u) * (G * D) + hh * D;
-                f[u] = __shfl(fp, p + u);
+                f[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fp), p + u));  // (p is the same in every lane)
 #pragma unroll
                 for (int t = 0; t < DPT; ++t) v[u][t] = pa[lane * DPT + t];
             }
@@ -74,7 +69,7 @@ __global__ __launch_bounds__(64) void attn_merge(const AttnArgs a)
         }
         for (; p < cnt; ++p) {
             const float *pa = a.part_acc + slot_of(base + p) * (G * D) + hh * D;
-            const float f = __shfl(fp, p);
+            const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fp), p));
 #pragma unroll
             for (int t = 0; t < DPT; ++t) o[t] = fmaf(f, pa[lane * DPT + t], o[t]);
         }

@@ -84,8 +84,7 @@ struct MfmaPair {
         float mx = x[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) mx = max_nc(mx, x[e]);
-        mx = max_nc(mx, __shfl_xor(mx, 16));
-        mx = max_nc(mx, __shfl_xor(mx, 32));
+        mx = max_rows(mx);
         const float m_new = max_nc(m, mx);
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         m = m_new;
@@ -115,8 +114,7 @@ struct MfmaPair {
                                                          float m, float l, const f32x4 (&o)[DB])
     {
         float ls = l;
-        ls += __shfl_xor(ls, 16);
-        ls += __shfl_xor(ls, 32);
+        ls = sum_rows(ls);
         if (!write) return;
         float *pacc = a.part_acc + slot * ((size_t)G * D) + (size_t)head * D + 4 * DB * gr;
 #pragma unroll

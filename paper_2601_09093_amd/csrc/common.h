@@ -48,6 +48,61 @@ constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppRowMirror = 0x140;  // lane c <- lane 15 - c
 constexpr int kDppHalfMirror = 0x141; // lane c <- lane 7 - c within each 8 lanes
+
+// max without the NaN-quieting pass (inputs here are never signalling NaNs that matter)
+__device__ __forceinline__ float max_nc(float x, float y) { return __builtin_amdgcn_fmed3f(x, y, INFINITY); }
+
+// gfx950's v_permlane16_swap / v_permlane32_swap with both operands the same register: the first result holds, in
+// both rows of a pair (both halves of the wave), the value of the even row (the lower half), the second that of the
+// odd row (the upper half).  Combining the two gives every lane the combination of its own value with that of lane ^ 16
+// (lane ^ 32), bit-identical in both lanes, as a vector-ALU operation instead of a trip through the LDS crossbar.
+__device__ __forceinline__ void swap16(float x, float &even, float &odd)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    even = __uint_as_float(r[0]);
+    odd = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void swap32(float x, float &lower, float &upper)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    lower = __uint_as_float(r[0]);
+    upper = __uint_as_float(r[1]);
+}
+// over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the same column of the four 16-lane rows), to all four
+__device__ __forceinline__ float max_rows(float x)
+{
+    float a, b;
+    swap16(x, a, b);
+    x = max_nc(a, b);
+    swap32(x, a, b);
+    return max_nc(a, b);
+}
+__device__ __forceinline__ float sum_rows(float x)
+{
+    float a, b;
+    swap16(x, a, b);
+    x = a + b;
+    swap32(x, a, b);
+    return a + b;
+}
+// over the 16 lanes of a row, to all of them (xor 1, xor 2, half mirror, mirror)
+__device__ __forceinline__ float max_row16(float x)
+{
+    x = max_nc(x, dpp<kDppXor1>(x));
+    x = max_nc(x, dpp<kDppXor2>(x));
+    x = max_nc(x, dpp<kDppHalfMirror>(x));
+    return max_nc(x, dpp<kDppRowMirror>(x));
+}
+__device__ __forceinline__ float sum_row16(float x)
+{
+    x += dpp<kDppXor1>(x);
+    x += dpp<kDppXor2>(x);
+    x += dpp<kDppHalfMirror>(x);
+    return x + dpp<kDppRowMirror>(x);
+}
+// over the 64 lanes of the wave, to all of them; the order of the additions is fixed
+__device__ __forceinline__ float wave_max(float x) { return max_rows(max_row16(x)); }
+__device__ __forceinline__ float wave_sum(float x) { return sum_rows(sum_row16(x)); }
 constexpr int kDppRowRor4 = 0x124;
 constexpr int kDppRowRor8 = 0x128;
 #define STEP_DPP_QUAD_BCAST(k) ((k) * 0x55)

@@ -99,21 +99,6 @@ __device__ __forceinline__ bool last_to_arrive(int32_t *ticket, int expected, in
     return *flag_s != 0;
 }
 
-// Sum over the 64 lanes in a fixed order, returned to every lane: within each row of 16 lanes with four DPP exchanges
-// (xor 1, xor 2, half mirror, mirror: no LDS round trips), then the four row sums in row order.
-__device__ __forceinline__ float wave_sum(float x)
-{
-    x += dpp<kDppXor1>(x);
-    x += dpp<kDppXor2>(x);
-    x += dpp<kDppHalfMirror>(x);
-    x += dpp<kDppRowMirror>(x);
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
-    return ((r0 + r1) + r2) + r3;
-}
-
 // Logits and probabilities of the boundaries base + bb0 .. + KB4 (one wave): lane l adds the row tiles l, l + 64, ...
 // in ascending order, then the lanes are added by wave_sum -- the same order whatever KB4 is.
 template <int KB4>
@@ -419,8 +404,7 @@ __global__ __launch_bounds__(kThreads) void score_hidden(const ScoreArgs a)
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) s = fmaf(w2v[i], activate(z[i] + b1v[i], a.act), s);
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 32);
+        s = sum_rows(s);
         if (kg == 0 && b < a.B) st_dev(&a.plogit[(size_t)mt * a.B + b], s);
     }
     // step 4
