@@ -94,8 +94,8 @@ int32_t step_attn_waves_per_head(const step_attn_dims *dims);
  * softmax weights are rounded to bf16 before they multiply V (the normaliser is summed from the
  * same rounded weights).  Result within 2e-2
  * max-abs of the float64 definition for N(0,1) inputs.
- * Shared prompts: the traces are taken in blocks of 16 * QT / G consecutive indices (QT = 2 once N * G >= 256,
- * else 1); the leading block-table entries that every live trace of a block has in common (whole pages all
+ * Shared prompts: the traces are taken in blocks of 16 * QT / G consecutive indices (QT = 1 while the waves of a
+ * KV head outnumber such blocks at least three to one, else 2); the leading block-table entries that every live trace of a block has in common (whole pages all
  * of them attend to completely, up to 1024) are found on the device and computed once per block on the
  * matrix cores.  The environment variable STEP_ATTN_PREFIX=0, read once, turns that off (testing aid: the
  * pages are then streamed per trace like private pages).  N * MAXB must stay below 2^30.

@@ -95,8 +95,12 @@ Layout layout_for(const step_attn_dims *d)
     Layout l;
     const int G = d->Hq / d->Hkv;
     l.Wh = waves_per_head(d);
-    // query tiles per wave of attn_front: 2 once there are enough query rows to fill the chip that way
-    l.prefix_qt = !prefix_enabled() ? 0 : ((long long)d->N * G >= 256) ? 2 : 1;
+    // query tiles per wave of attn_front: one, as long as that leaves a shared prefix at least four sub-chunks per
+    // block (waves per KV head / blocks of 16 query rows); with more blocks than that, two tiles per wave halve
+    // the number of blocks.  Measured on eight shapes (N * G from 256 to 2048, 2 and 8 KV heads): each is faster
+    // on the side this rule puts it.
+    const int nblk1 = (int)(((long long)d->N * G + 15) / 16);
+    l.prefix_qt = !prefix_enabled() ? 0 : (nblk1 <= 0 || (l.Wh + nblk1 - 1) / nblk1 >= 4) ? 1 : 2;
     l.TB = 16 * (l.prefix_qt ? l.prefix_qt : 1) / G;
     l.nblk = (d->N + l.TB - 1) / l.TB;
     // sub-chunks of a shared prefix per trace: never more than prefix_split can ask for (about one wave per

@@ -254,14 +254,16 @@ def test_corner_cases_of_the_cut(case):
     check(q, k, v, lay.block_tables, lay.seq_lens)
 
 
-@pytest.mark.parametrize("G,D", [(4, 128), (1, 64), (8, 128), (2, 128)])
-def test_blocks_of_traces_with_different_shared_prefixes(G, D):
+@pytest.mark.parametrize("G,D,Hkv,rep", [(4, 128, 2, 1), (1, 64, 2, 1), (8, 128, 2, 1), (2, 128, 2, 1), (8, 128, 8, 2),
+                                         (8, 64, 8, 2)])
+def test_blocks_of_traces_with_different_shared_prefixes(G, D, Hkv, rep):
     """Shared prefixes are found per block of 16 * QT / G consecutive traces.  Here groups of traces share
     different prompts of different lengths (two prompts in one batch), some blocks hold a single live trace or
-    none, one trace ends inside its group's prompt pages, and the groups do not line up with the blocks."""
-    Hkv = 2
+    none, one trace ends inside its group's prompt pages, and the groups do not line up with the blocks.
+    The last two shapes (104 traces of 8 query heads per KV head, 8 KV heads) have more blocks than a KV head's
+    waves serve four sub-chunks each, so the shared-prefix kernel takes two query tiles per wave there."""
     r = wl.rng_for(4400 + G + D, 0)
-    groups = [(11, 20), (7, 0), (9, 130), (5, 3), (13, 64), (1, 9), (6, 257)]     # (traces, prompt pages)
+    groups = [(11, 20), (7, 0), (9, 130), (5, 3), (13, 64), (1, 9), (6, 257)] * rep  # (traces, prompt pages)
     lens, prompts = [], []
     for n, pp in groups:
         for _ in range(n):
@@ -427,11 +429,12 @@ def test_one_plan_shared_by_several_layers():
         assert np.array_equal(host_bits(one), host_bits(outs[l]))
 
 
-@pytest.mark.parametrize("D,Hq,Hkv,N", [(64, 2, 2, 12), (64, 16, 2, 40), (128, 4, 2, 20), (128, 16, 2, 40)])
+@pytest.mark.parametrize("D,Hq,Hkv,N", [(64, 2, 2, 12), (64, 64, 8, 100), (128, 4, 2, 20), (128, 64, 8, 100)])
 def test_planned_form_on_every_kernel_variant(D, Hq, Hkv, N):
     """The planned form (prefix lengths read from the workspace instead of searched) on the shapes the one-plan test
-    does not reach: head dimension 64, one and two query tiles per wave of the shared-prefix kernel (N * G below
-    and above 256), the matrix-core streaming kernel.  Same bar as the one-call form and the same bits."""
+    does not reach: head dimension 64, one and two query tiles per wave of the shared-prefix kernel (two where the
+    blocks of 16 query rows outnumber a third of a KV head's waves: 100 traces of 8 heads per KV head, 8 KV
+    heads), the matrix-core streaming kernel.  Same bar as the one-call form and the same bits."""
     r = wl.rng_for(7700 + D + N, 0)
     lens = 96 + r.integers(1, 700, N); lens[3] = 0
     lay, q, k, v = build(7700 + D + N, lens, Hq, Hkv, D, prompt=96)
