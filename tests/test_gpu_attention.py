@@ -113,11 +113,14 @@ def test_page_permutation_is_bit_identical_and_private_prefix_copies_agree():
 
 
 @pytest.mark.parametrize("switches", [{"STEP_ATTN_PREFIX": "0"}, {"STEP_ATTN_G4_MFMA": "1"},
-                                      {"STEP_ATTN_PREFIX": "0", "STEP_ATTN_G4_MFMA": "1"}])
+                                      {"STEP_ATTN_PREFIX": "0", "STEP_ATTN_G4_MFMA": "1"},
+                                      {"STEP_ATTN_WAVES_PER_CU": "8"}, {"STEP_ATTN_WAVES_PER_CU": "1"}])
 def test_alternative_kernel_routes_meet_the_same_bar(switches):
     """STEP_ATTN_PREFIX=0 keeps the shared prefix in the streaming kernels, STEP_ATTN_G4_MFMA=1 sends
-    group size 4 to the matrix-core streaming kernel (both read once per process, hence the child
-    process); every route meets the same bar."""
+    group size 4 to the matrix-core streaming kernel, STEP_ATTN_WAVES_PER_CU changes into how many runs the
+    private pages are cut (8 per unit: a second round of waves, and with one KV head the most runs a call
+    takes; 1: a quarter of the usual) -- all read once per process, hence the child process; every route
+    meets the same bar."""
     import json, os, subprocess, sys
     code = (
         "import sys, json; sys.path.insert(0, %r)\n"
